@@ -1,0 +1,143 @@
+"""ctypes front-end of the plain-C fp64 oracle: TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this
+package; the product path (paper_2402_01869_amd) never does and shares no code with it.
+
+paged_attn / paged_attn_items : textbook causal scaled-dot-product attention read through
+    block tables (paper Sections 3.1, 4.2 and 4.3), fp64, bf16 bit patterns in.
+pack_blocks / unpack_blocks   : the swap gather / scatter of Section 3.2 as memcpy loops.
+Every function is pinned by tests/test_oracle_pins.py; none is "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Optional
+
+import numpy as np
+
+from .build import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(_build())
+        i32p, u16p, u8p, f64p = (C.POINTER(C.c_int32), C.POINTER(C.c_uint16),
+                                 C.POINTER(C.c_uint8), C.POINTER(C.c_double))
+        _lib.oracle_paged_attn_items.argtypes = [
+            u16p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p, i32p, C.c_int,
+            u16p, C.c_double, C.c_int64, i32p, i32p, f64p]
+        _lib.oracle_paged_attn_items.restype = C.c_int
+        _lib.oracle_paged_attn.argtypes = [
+            u16p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p, i32p, C.c_int,
+            u16p, C.c_double, f64p]
+        _lib.oracle_paged_attn.restype = C.c_int
+        _lib.oracle_pack_blocks.argtypes = [u8p, C.c_int64, C.c_int64, i32p, C.c_int64, u8p]
+        _lib.oracle_pack_blocks.restype = C.c_int
+        _lib.oracle_unpack_blocks.argtypes = [u8p, C.c_int64, C.c_int64, i32p, C.c_int64, u8p]
+        _lib.oracle_unpack_blocks.restype = C.c_int
+        _lib.oracle_num_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a: np.ndarray, ctype):
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def _check(rc: int) -> None:
+    if rc == -1:
+        raise MemoryError("oracle: allocation failed")
+    if rc == -2:
+        raise OracleError("oracle: invalid descriptor or block id")
+    if rc == -3:
+        raise OracleError("oracle: duplicate destination block id")
+    if rc != 0:
+        raise OracleError(f"oracle: error {rc}")
+
+
+def paged_attn_items(pool_bits, ctx_len, q_len, q_start, block_tables, q_bits, scale,
+                     item_seq, item_row) -> np.ndarray:
+    """Attention for the listed (sequence, row-in-span) pairs -> fp64 [n_items][H][D].
+
+    pool_bits uint16 [blocks][2][H][B][D]; q_bits uint16 [rows][H][D]; block_tables int32
+    [num_seqs][max_blocks] (unused entries may hold anything).
+    """
+    pool_bits = _c(pool_bits, np.uint16)
+    nblk, two, H, B, D = pool_bits.shape
+    assert two == 2
+    ctx_len, q_len, q_start = _c(ctx_len, np.int32), _c(q_len, np.int32), _c(q_start, np.int32)
+    block_tables = _c(block_tables, np.int32)
+    q_bits = _c(q_bits, np.uint16)
+    assert q_bits.ndim == 3 and q_bits.shape[1:] == (H, D)
+    item_seq, item_row = _c(item_seq, np.int32), _c(item_row, np.int32)
+    n = item_seq.shape[0]
+    out = np.empty((n, H, D), dtype=np.float64)
+    rc = lib().oracle_paged_attn_items(
+        _p(pool_bits, C.c_uint16), nblk, B, H, D, ctx_len.shape[0], _p(ctx_len, C.c_int32),
+        _p(q_len, C.c_int32), _p(q_start, C.c_int32), _p(block_tables, C.c_int32),
+        block_tables.shape[1], _p(q_bits, C.c_uint16), float(scale), n,
+        _p(item_seq, C.c_int32), _p(item_row, C.c_int32), _p(out, C.c_double))
+    _check(rc)
+    return out
+
+
+def paged_attn(pool_bits, ctx_len, q_len, q_start, block_tables, q_bits, scale,
+               total_q_rows: Optional[int] = None) -> np.ndarray:
+    """Attention for every row of the batch -> fp64 [total_q_rows][H][D]."""
+    pool_bits = _c(pool_bits, np.uint16)
+    nblk, two, H, B, D = pool_bits.shape
+    assert two == 2
+    ctx_len, q_len, q_start = _c(ctx_len, np.int32), _c(q_len, np.int32), _c(q_start, np.int32)
+    block_tables = _c(block_tables, np.int32)
+    q_bits = _c(q_bits, np.uint16)
+    rows = int(q_bits.shape[0]) if total_q_rows is None else int(total_q_rows)
+    out = np.full((rows, H, D), np.nan, dtype=np.float64)
+    rc = lib().oracle_paged_attn(
+        _p(pool_bits, C.c_uint16), nblk, B, H, D, ctx_len.shape[0], _p(ctx_len, C.c_int32),
+        _p(q_len, C.c_int32), _p(q_start, C.c_int32), _p(block_tables, C.c_int32),
+        block_tables.shape[1], _p(q_bits, C.c_uint16), float(scale), _p(out, C.c_double))
+    _check(rc)
+    return out
+
+
+def attn_batch(batch, pool_bits, q_bits) -> np.ndarray:
+    """Convenience: paged_attn on a workloads.Batch-like object (duck-typed, nothing imported)."""
+    return paged_attn(pool_bits, batch.ctx_len, batch.q_len, batch.q_start, batch.block_tables,
+                      q_bits, batch.scale, batch.total_q_rows)
+
+
+def pack_blocks(pool_bytes: np.ndarray, ids) -> np.ndarray:
+    """staging[i] = pool[ids[i]] as raw bytes; pool_bytes is uint8 [blocks][block_bytes]."""
+    pool_bytes = _c(pool_bytes, np.uint8)
+    ids = _c(ids, np.int32)
+    nblk, bb = pool_bytes.shape
+    staging = np.empty((ids.shape[0], bb), dtype=np.uint8)
+    _check(lib().oracle_pack_blocks(_p(pool_bytes, C.c_uint8), nblk, bb, _p(ids, C.c_int32),
+                                    ids.shape[0], _p(staging, C.c_uint8)))
+    return staging
+
+
+def unpack_blocks(pool_bytes: np.ndarray, ids, staging: np.ndarray) -> None:
+    """pool[ids[i]] = staging[i], in place; ids must be distinct."""
+    assert pool_bytes.dtype == np.uint8 and pool_bytes.flags.c_contiguous
+    ids = _c(ids, np.int32)
+    staging = _c(staging, np.uint8)
+    nblk, bb = pool_bytes.shape
+    assert staging.shape == (ids.shape[0], bb)
+    _check(lib().oracle_unpack_blocks(_p(pool_bytes, C.c_uint8), nblk, bb, _p(ids, C.c_int32),
+                                      ids.shape[0], _p(staging, C.c_uint8)))
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())

@@ -1,0 +1,207 @@
+/*
+ * CPU oracle for the intercept hot path: TEST INFRASTRUCTURE ONLY.
+ *
+ * Only the test-suite, the smoke check and the benchmark's cpu_baseline leg may
+ * call this file.  It shares no code with the HIP library and is deliberately
+ * plain: fp64 arithmetic, the textbook definition written out, two passes over
+ * the keys (max, then sum) instead of an online softmax, no blocking and no
+ * intrinsics.  The only parallelism is one OpenMP loop over (query row, head).
+ *
+ * What it defines
+ *  - Paged attention (paper Section 3.1: the KV cache is virtual memory mapped
+ *    to non-contiguous physical blocks): logical token t of a sequence lives in
+ *    physical block block_table[t / B], slot t % B.
+ *  - Mixed batches (Section 4.2): a decode sequence contributes one query row,
+ *    a recomputation chunk contributes q_len rows.  Row i of a chunk sits at
+ *    absolute position p = ctx_len - q_len + i and attends to keys 0..p
+ *    inclusive, so that recomputing a context chunk by chunk over several
+ *    iterations (Section 4.3, partially recomputed requests stay queued)
+ *    reproduces what a one-shot causal prefill would have produced.
+ *  - Swap of scattered blocks (Section 3.2, swap-based approach): gather the
+ *    listed blocks into a contiguous staging buffer, and scatter them back.
+ *
+ * The attention formula itself is not printed in the paper (it inherits the
+ * serving stack's kernels, Section 4.5); it is the standard scaled dot-product
+ * causal attention  out = softmax(scale * q K^T) V.
+ *
+ * Pool layout (layout 0): [block][K=0 / V=1][head][slot][dim], bf16 bit patterns.
+ * Every pinned property of this file is listed in tests/test_oracle_pins.py.
+ */
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+static double bf16_bits_to_double(uint16_t b)
+{
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* address of element (block, kv, head, slot, 0) */
+static const uint16_t *kv_row(const uint16_t *pool, int64_t block, int kv, int head, int slot,
+                              int H, int B, int D)
+{
+    int64_t idx = ((((block * 2 + kv) * H + head) * (int64_t)B + slot) * (int64_t)D);
+    return pool + idx;
+}
+
+/*
+ * One (query row, head): returns 0, or -1 if scratch allocation fails.
+ *   p        absolute position of the row (keys 0..p are visible)
+ *   table    block table of the row's sequence
+ *   qrow     D bf16 values of the query for this head
+ *   out      D doubles
+ */
+static int attend_one(const uint16_t *pool, int H, int B, int D, const int32_t *table, int head,
+                      int64_t p, const uint16_t *qrow, double scale, double *out)
+{
+    int64_t nkeys = p + 1;
+    double *score = (double *)malloc(sizeof(double) * (size_t)nkeys);
+    if (!score) return -1;
+
+    /* pass 1: scores and their maximum */
+    double smax = -INFINITY;
+    for (int64_t t = 0; t < nkeys; ++t) {
+        const uint16_t *k = kv_row(pool, table[t / B], 0, head, (int)(t % B), H, B, D);
+        double dot = 0.0;
+        for (int d = 0; d < D; ++d) dot += bf16_bits_to_double(qrow[d]) * bf16_bits_to_double(k[d]);
+        score[t] = scale * dot;
+        if (score[t] > smax) smax = score[t];
+    }
+    /* pass 2: normaliser */
+    double denom = 0.0;
+    for (int64_t t = 0; t < nkeys; ++t) {
+        score[t] = exp(score[t] - smax);
+        denom += score[t];
+    }
+    /* weighted sum of values */
+    for (int d = 0; d < D; ++d) out[d] = 0.0;
+    for (int64_t t = 0; t < nkeys; ++t) {
+        const uint16_t *v = kv_row(pool, table[t / B], 1, head, (int)(t % B), H, B, D);
+        double w = score[t] / denom;
+        for (int d = 0; d < D; ++d) out[d] += w * bf16_bits_to_double(v[d]);
+    }
+    free(score);
+    return 0;
+}
+
+/*
+ * Attention for a list of (sequence, row-in-span) items; out is [n_items][H][D] fp64.
+ * Returns 0 on success, -1 on allocation failure, -2 on an invalid descriptor.
+ */
+int oracle_paged_attn_items(const uint16_t *pool, int64_t num_blocks, int B, int H, int D,
+                            int num_seqs, const int32_t *ctx_len, const int32_t *q_len,
+                            const int32_t *q_start, const int32_t *block_tables,
+                            int max_blocks_per_seq, const uint16_t *q, double scale,
+                            int64_t n_items, const int32_t *item_seq, const int32_t *item_row,
+                            double *out)
+{
+    for (int64_t it = 0; it < n_items; ++it) {
+        int s = item_seq[it];
+        if (s < 0 || s >= num_seqs) return -2;
+        if (ctx_len[s] < 1 || q_len[s] < 1 || q_len[s] > ctx_len[s]) return -2;
+        if (item_row[it] < 0 || item_row[it] >= q_len[s]) return -2;
+        int nb = (ctx_len[s] + B - 1) / B;
+        if (nb > max_blocks_per_seq) return -2;
+        for (int j = 0; j < nb; ++j) {
+            int32_t id = block_tables[(int64_t)s * max_blocks_per_seq + j];
+            if (id < 0 || id >= num_blocks) return -2;
+        }
+    }
+    int failed = 0;
+    int64_t work = n_items * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t w = 0; w < work; ++w) {
+        int64_t it = w / H;
+        int head = (int)(w % H);
+        int s = item_seq[it];
+        int i = item_row[it];
+        int64_t p = (int64_t)ctx_len[s] - q_len[s] + i;
+        const int32_t *table = block_tables + (int64_t)s * max_blocks_per_seq;
+        const uint16_t *qrow = q + (((int64_t)q_start[s] + i) * H + head) * (int64_t)D;
+        double *o = out + (it * H + head) * (int64_t)D;
+        if (attend_one(pool, H, B, D, table, head, p, qrow, scale, o) != 0) {
+#pragma omp atomic write
+            failed = 1;
+        }
+    }
+    return failed ? -1 : 0;
+}
+
+/* Every row of every sequence; out is [total_q_rows][H][D] fp64, indexed by q_start[s] + i. */
+int oracle_paged_attn(const uint16_t *pool, int64_t num_blocks, int B, int H, int D, int num_seqs,
+                      const int32_t *ctx_len, const int32_t *q_len, const int32_t *q_start,
+                      const int32_t *block_tables, int max_blocks_per_seq, const uint16_t *q,
+                      double scale, double *out)
+{
+    int64_t n_items = 0;
+    for (int s = 0; s < num_seqs; ++s) {
+        if (q_len[s] < 1) return -2;
+        n_items += q_len[s];
+    }
+    int32_t *iseq = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_items ? n_items : 1));
+    int32_t *irow = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_items ? n_items : 1));
+    int64_t *dst = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_items ? n_items : 1));
+    double *tmp = (double *)malloc(sizeof(double) * (size_t)(n_items ? n_items : 1) * H * D);
+    if (!iseq || !irow || !dst || !tmp) { free(iseq); free(irow); free(dst); free(tmp); return -1; }
+    int64_t n = 0;
+    for (int s = 0; s < num_seqs; ++s)
+        for (int i = 0; i < q_len[s]; ++i) {
+            iseq[n] = s; irow[n] = i; dst[n] = (int64_t)q_start[s] + i; ++n;
+        }
+    int rc = oracle_paged_attn_items(pool, num_blocks, B, H, D, num_seqs, ctx_len, q_len, q_start,
+                                     block_tables, max_blocks_per_seq, q, scale, n_items, iseq, irow, tmp);
+    if (rc == 0)
+        for (int64_t k = 0; k < n_items; ++k)
+            memcpy(out + dst[k] * H * D, tmp + k * H * D, sizeof(double) * (size_t)H * D);
+    free(iseq); free(irow); free(dst); free(tmp);
+    return rc;
+}
+
+/* staging[i] <- pool[ids[i]], i < n; list order; duplicate sources allowed. */
+int oracle_pack_blocks(const uint8_t *pool, int64_t num_blocks, int64_t block_bytes,
+                       const int32_t *ids, int64_t n, uint8_t *staging)
+{
+    for (int64_t i = 0; i < n; ++i)
+        if (ids[i] < 0 || ids[i] >= num_blocks) return -2;
+    for (int64_t i = 0; i < n; ++i)
+        memcpy(staging + i * block_bytes, pool + (int64_t)ids[i] * block_bytes, (size_t)block_bytes);
+    return 0;
+}
+
+/* pool[ids[i]] <- staging[i], i < n; destinations must be distinct (-3 otherwise). */
+int oracle_unpack_blocks(uint8_t *pool, int64_t num_blocks, int64_t block_bytes,
+                         const int32_t *ids, int64_t n, const uint8_t *staging)
+{
+    for (int64_t i = 0; i < n; ++i)
+        if (ids[i] < 0 || ids[i] >= num_blocks) return -2;
+    uint8_t *seen = (uint8_t *)calloc((size_t)(num_blocks ? num_blocks : 1), 1);
+    if (!seen) return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        if (seen[ids[i]]) { free(seen); return -3; }
+        seen[ids[i]] = 1;
+    }
+    free(seen);
+    for (int64_t i = 0; i < n; ++i)
+        memcpy(pool + (int64_t)ids[i] * block_bytes, staging + i * block_bytes, (size_t)block_bytes);
+    return 0;
+}
+
+int oracle_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp single
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}

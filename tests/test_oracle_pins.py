@@ -1,0 +1,318 @@
+"""Pins of the CPU oracle against closed forms, invariants, library routines and brute force.
+
+The paper prints no worked attention or swap values, so the oracle is pinned by what the
+mathematics fixes.  Each test names the mistake it is meant to catch.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2402_01869_amd import workloads as W
+from helpers import bits, dense_causal_attention, paged_pool_from_dense
+
+B = 16
+
+
+def _single(K, V, q, scale, q_len=None, table=None, num_blocks=None, rng=None):
+    """Run the oracle on one sequence given dense bf16-bit K, V [ctx][H][D] and q [n][H][D]."""
+    ctx, H, D = K.shape
+    nb = -(-ctx // B)
+    num_blocks = num_blocks or (nb + 3)
+    if table is None:
+        rng = rng or np.random.default_rng(0)
+        table = rng.permutation(num_blocks)[:nb].astype(np.int32)
+    pool = paged_pool_from_dense(K, V, table, B, num_blocks)
+    n = q.shape[0] if q_len is None else q_len
+    return oracle.paged_attn(pool, [ctx], [n], [0], table[None, :], q, scale)
+
+
+def test_single_key_returns_v0():
+    # softmax over one key is 1: out == v_0 exactly.  Catches K/V offset mix-ups at slot 0.
+    rng = np.random.default_rng(1)
+    K, V, q = (W.randn_bf16((1, 3, 8), rng) for _ in range(3))
+    out = _single(K, V, q, 0.35)
+    assert np.array_equal(out[0], W.bf16_bits_to_f64(V[0]))
+
+
+def test_constant_v_returns_v():
+    # weights sum to one: a constant V comes back whatever Q and K are.  Catches a wrong normaliser.
+    rng = np.random.default_rng(2)
+    ctx, H, D, n = 45, 2, 16, 9
+    K = W.randn_bf16((ctx, H, D), rng)
+    c = W.randn_bf16((1, H, D), rng)
+    V = np.repeat(c, ctx, axis=0)
+    q = W.randn_bf16((n, H, D), rng)
+    out = _single(K, V, q, 1 / 4)
+    want = np.broadcast_to(W.bf16_bits_to_f64(c), out.shape)
+    assert np.allclose(out, want, rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("ctx,n", [(37, 1), (37, 37), (50, 20), (16, 16), (33, 2)])
+def test_uniform_scores_give_running_mean(ctx, n):
+    # q = 0 -> every visible key weighs the same; with v_t = t the answer is p_i / 2 exactly.
+    # Catches a causal off-by-one (row i must see keys 0..p_i inclusive, p_i = ctx - n + i).
+    H, D = 2, 8
+    rng = np.random.default_rng(3)
+    K = W.randn_bf16((ctx, H, D), rng)
+    V = bits(np.broadcast_to(np.arange(ctx, dtype=np.float32)[:, None, None], (ctx, H, D)))
+    q = np.zeros((n, H, D), dtype=np.uint16)
+    out = _single(K, V, q, 0.5)
+    for i in range(n):
+        p = ctx - n + i
+        assert np.allclose(out[i], p / 2.0, rtol=0, atol=1e-12), (i, p)
+
+
+def test_scale_zero_is_uniform():
+    rng = np.random.default_rng(4)
+    ctx, H, D = 21, 1, 8
+    K, q = W.randn_bf16((ctx, H, D), rng), W.randn_bf16((1, H, D), rng)
+    V = bits(np.broadcast_to(np.arange(ctx, dtype=np.float32)[:, None, None], (ctx, H, D)))
+    out = _single(K, V, q, 0.0)
+    assert np.allclose(out, (ctx - 1) / 2.0, atol=1e-12)
+
+
+def test_peaked_score_pins_block_table_gather():
+    # One key is aligned with q and large, the rest are orthogonal: out -> v_{t*} up to a bounded
+    # residual.  V encodes (head, physical block, slot), so a wrong block, slot, head or K/V plane shows.
+    H, D, ctx = 3, 8, 70
+    nb = -(-ctx // B)
+    num_blocks = 11
+    rng = np.random.default_rng(5)
+    table = rng.permutation(num_blocks)[:nb].astype(np.int32)
+    lam, scale = 64.0, 0.5
+    for tstar in [0, 1, 15, 16, 17, 31, 32, 48, 69]:
+        K = np.zeros((ctx, H, D), dtype=np.float32)
+        q = np.zeros((1, H, D), dtype=np.float32)
+        for h in range(H):
+            q[0, h, h] = 1.0                 # unit vector, different axis per head
+            K[:, h, (h + 1) % D] = 1.0       # orthogonal to q
+            K[tstar, h, :] = 0.0
+            K[tstar, h, h] = lam
+        V = np.zeros((ctx, H, D), dtype=np.float32)
+        for t in range(ctx):
+            for h in range(H):
+                V[t, h, 0] = table[t // B]    # physical block
+                V[t, h, 1] = t % B            # slot
+                V[t, h, 2] = h
+                V[t, h, 3] = t
+        out = _single(bits(K), bits(V), bits(q), scale, table=table, num_blocks=num_blocks)
+        resid = (ctx - 1) * math.exp(-lam * scale) * ctx   # weight bound x value bound
+        want = V[tstar].astype(np.float64)
+        assert np.allclose(out[0], want, rtol=0, atol=resid + 1e-12), tstar
+
+
+def test_two_keys_logistic_closed_form():
+    # out = sigma(s0 - s1) v0 + sigma(s1 - s0) v1, computed by hand here.  Catches a dropped scale,
+    # a sign error in the exponent, or transposed q/k operands.
+    q = np.array([[[0.5, -1.0, 2.0, 0.25]]], dtype=np.float32)
+    K = np.array([[[1.0, 0.5, 0.25, -2.0]], [[-0.5, 1.5, 1.0, 0.75]]], dtype=np.float32)
+    V = np.array([[[1.0, -2.0, 3.0, 0.5]], [[-4.0, 0.25, 8.0, 1.5]]], dtype=np.float32)
+    scale = 0.7
+    s0 = scale * float((q[0, 0] * K[0, 0]).sum())
+    s1 = scale * float((q[0, 0] * K[1, 0]).sum())
+    w0 = 1.0 / (1.0 + math.exp(s1 - s0))
+    want = w0 * V[0, 0].astype(np.float64) + (1.0 - w0) * V[1, 0].astype(np.float64)
+    out = _single(bits(K), bits(V), bits(q), scale)
+    assert np.allclose(out[0, 0], want, rtol=0, atol=1e-14)
+    # row 0 of a 2-row span sees only key 0
+    q2 = np.concatenate([q, q], axis=0)
+    out2 = _single(bits(K), bits(V), bits(q2), scale)
+    assert np.array_equal(out2[0, 0], V[0, 0].astype(np.float64))
+    assert np.allclose(out2[1, 0], want, rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("ctx,n,H,D", [(100, 1, 4, 64), (100, 100, 2, 32), (77, 32, 3, 16), (16, 5, 1, 128)])
+def test_paged_equals_dense_numpy(ctx, n, H, D):
+    # Paging is a pure re-mapping (Section 3.1): the paged result equals dense contiguous attention.
+    rng = np.random.default_rng(6)
+    K, V = W.randn_bf16((ctx, H, D), rng), W.randn_bf16((ctx, H, D), rng)
+    q = W.randn_bf16((n, H, D), rng)
+    scale = 1 / math.sqrt(D)
+    out = _single(K, V, q, scale, rng=rng)
+    want = dense_causal_attention(W.bf16_bits_to_f64(q), W.bf16_bits_to_f64(K), W.bf16_bits_to_f64(V),
+                                  scale, ctx - n)
+    assert np.allclose(out, want, rtol=0, atol=1e-13)
+
+
+def test_matches_torch_cpu_fp64():
+    # Second independent reference: plain torch CPU ops in fp64 (softmax(QK^T scale + mask) @ V).
+    import torch
+    rng = np.random.default_rng(7)
+    ctx, n, H, D = 130, 40, 2, 64
+    K, V = W.randn_bf16((ctx, H, D), rng), W.randn_bf16((ctx, H, D), rng)
+    q = W.randn_bf16((n, H, D), rng)
+    scale = 1 / math.sqrt(D)
+    out = _single(K, V, q, scale, rng=rng)
+    tq, tk, tv = (torch.from_numpy(W.bf16_bits_to_f64(a)).permute(1, 0, 2) for a in (q, K, V))
+    s = tq @ tk.transpose(1, 2) * scale
+    pos = (ctx - n) + torch.arange(n)[:, None]
+    s = s.masked_fill(torch.arange(ctx)[None, :] > pos, float("-inf"))
+    want = (torch.softmax(s, dim=-1) @ tv).permute(1, 0, 2).numpy()
+    assert np.allclose(out, want, rtol=0, atol=1e-13)
+
+
+def test_brute_force_tiny_pure_python():
+    # Third formulation: sum_t e^{s_t} v_t / sum_t e^{s_t} with no max subtraction, python floats + fsum.
+    rng = np.random.default_rng(8)
+    ctx, n, H, D = 19, 4, 2, 4
+    K, V, q = (W.randn_bf16(s, rng) for s in ((ctx, H, D), (ctx, H, D), (n, H, D)))
+    scale = 0.5
+    out = _single(K, V, q, scale, rng=rng)
+    Kf, Vf, qf = (W.bf16_bits_to_f64(a) for a in (K, V, q))
+    for i in range(n):
+        p = ctx - n + i
+        for h in range(H):
+            e = [math.exp(scale * math.fsum(qf[i, h, d] * Kf[t, h, d] for d in range(D))) for t in range(p + 1)]
+            z = math.fsum(e)
+            for d in range(D):
+                want = math.fsum(e[t] * Vf[t, h, d] for t in range(p + 1)) / z
+                assert abs(out[i, h, d] - want) < 1e-12
+
+
+def test_physical_permutation_invariance_bit_identical():
+    # Relabelling physical blocks consistently changes nothing, bit for bit.
+    rng = np.random.default_rng(9)
+    cfg = W.TINY
+    batch = W.make_batch(cfg, seed=99)
+    pool, q = W.make_host_inputs(batch, seed=99)
+    out1 = oracle.attn_batch(batch, pool, q)
+    perm = rng.permutation(cfg.pool_blocks)
+    pool2 = np.empty_like(pool)
+    pool2[perm] = pool                       # block b moves to perm[b]
+    tables2 = np.where(batch.block_tables >= 0, perm[np.clip(batch.block_tables, 0, None)], -1).astype(np.int32)
+    out2 = oracle.paged_attn(pool2, batch.ctx_len, batch.q_len, batch.q_start, tables2, q, batch.scale)
+    assert np.array_equal(out1, out2)
+
+
+@pytest.mark.parametrize("chunk", [1, 7, 16, 32, 83])
+def test_chunked_recompute_equals_one_shot_prefill(chunk):
+    # Recomputing a context chunk by chunk over successive iterations, with ctx_len growing
+    # (Section 4.2 and the partial-recompute rule of Section 4.3), reproduces the one-shot causal
+    # prefill.  chunk = 1 also shows that a decode row equals the matching prefill row.
+    rng = np.random.default_rng(10)
+    L, H, D = 83, 2, 16
+    K, V, q = (W.randn_bf16((L, H, D), rng) for _ in range(3))
+    nb = -(-L // B)
+    table = rng.permutation(nb + 2)[:nb].astype(np.int32)
+    pool = paged_pool_from_dense(K, V, table, B, nb + 2)
+    scale = 0.25
+    full = oracle.paged_attn(pool, [L], [L], [0], table[None], q, scale)
+    pieces = []
+    done = 0
+    while done < L:
+        n = min(chunk, L - done)
+        ctx = done + n
+        # later tokens are not yet "recomputed": poison them to prove they are never read
+        pool_c = pool.copy()
+        for t in range(ctx, nb * B):
+            pool_c[table[t // B], :, :, t % B, :] = 0x7FFF
+        pieces.append(oracle.paged_attn(pool_c, [ctx], [n], [0], table[None], q[done:ctx], scale))
+        done = ctx
+    got = np.concatenate(pieces, axis=0)
+    assert np.allclose(got, full, rtol=0, atol=1e-14)
+    assert np.isfinite(got).all()
+
+
+def test_common_score_shift_leaves_output_unchanged():
+    # An extra dimension with q = 1, k_t = c adds the same constant to every score.
+    rng = np.random.default_rng(11)
+    ctx, H, D = 40, 2, 8
+    K, V, q = (W.bf16_bits_to_f64(W.randn_bf16(s, rng)) for s in ((ctx, H, D), (ctx, H, D), (3, H, D)))
+    base = _single(bits(K), bits(V), bits(q), 0.3)
+    K2 = np.concatenate([K, np.full((ctx, H, 1), 24.0)], axis=-1)
+    q2 = np.concatenate([q, np.ones((3, H, 1))], axis=-1)
+    V2 = np.concatenate([V, np.zeros((ctx, H, 1))], axis=-1)
+    shifted = _single(bits(K2), bits(V2), bits(q2), 0.3)
+    assert np.allclose(shifted[..., :D], base, rtol=0, atol=1e-13)
+
+
+def test_batch_equals_per_sequence_calls_and_poison_is_ignored():
+    # A multi-sequence batch equals one call per sequence (catches q_start / table-row stride errors),
+    # and NaN in every don't-care slot leaves the output finite and unchanged.
+    batch = W.make_batch(W.TINY)
+    clean, q = W.make_host_inputs(batch, seed=W.TINY.seed, poison_unused=False)
+    poisoned = clean.copy()
+    W.poison_pool(poisoned, batch)
+    assert not np.array_equal(clean, poisoned)
+    out_clean = oracle.attn_batch(batch, clean, q)
+    out_pois = oracle.attn_batch(batch, poisoned, q)
+    assert np.isfinite(out_pois).all()
+    assert np.array_equal(out_clean, out_pois)
+    for s in range(batch.num_seqs):
+        n, c, r0 = int(batch.q_len[s]), int(batch.ctx_len[s]), int(batch.q_start[s])
+        ids = batch.blocks_of(s)
+        one = oracle.paged_attn(poisoned, [c], [n], [0], ids[None], q[r0:r0 + n], batch.scale)
+        assert np.array_equal(one, out_pois[r0:r0 + n])
+    assert batch.q_len.tolist()[:2] == [1, 1] and (batch.q_len[2:] > 1).all()
+
+
+def test_items_subset_matches_full():
+    batch = W.make_batch(W.TINY)
+    pool, q = W.make_host_inputs(batch, seed=W.TINY.seed)
+    full = oracle.attn_batch(batch, pool, q)
+    iseq = [3, 0, 2, 2]
+    irow = [int(batch.q_len[3]) - 1, 0, 0, 5]
+    sub = oracle.paged_attn_items(pool, batch.ctx_len, batch.q_len, batch.q_start, batch.block_tables,
+                                  q, batch.scale, iseq, irow)
+    for k, (s, i) in enumerate(zip(iseq, irow)):
+        assert np.array_equal(sub[k], full[batch.q_start[s] + i])
+
+
+def test_statistics_at_moderate_shape():
+    # N(0,1) inputs with scale 1/sqrt(D): scores ~ N(0,1), so out has mean ~ 0 and
+    # variance ~ sum w_t^2 ~ e / ctx.  A coarse check that shapes and scale are wired as intended.
+    rng = np.random.default_rng(12)
+    ctx, H, D = 2048, 4, 128
+    K, V = W.randn_bf16((ctx, H, D), rng), W.randn_bf16((ctx, H, D), rng)
+    q = W.randn_bf16((1, H, D), rng)
+    out = _single(K, V, q, 1 / math.sqrt(D), rng=rng)
+    assert abs(out.mean()) < 0.02
+    assert 0.3 * math.e / ctx < out.var() < 3.0 * math.e / ctx
+
+
+def test_oracle_rejects_bad_descriptors():
+    batch = W.make_batch(W.TINY)
+    pool, q = W.make_host_inputs(batch, seed=1)
+    bad = batch.block_tables.copy()
+    bad[0, 0] = W.TINY.pool_blocks
+    with pytest.raises(oracle.OracleError):
+        oracle.paged_attn(pool, batch.ctx_len, batch.q_len, batch.q_start, bad, q, batch.scale)
+    ql = batch.q_len.copy()
+    ql[0] = batch.ctx_len[0] + 1
+    with pytest.raises(oracle.OracleError):
+        oracle.paged_attn(pool, batch.ctx_len, ql, batch.q_start, batch.block_tables, q, batch.scale)
+
+
+# ------------------------------------------------------------------ swap (Section 3.2)
+
+def test_pack_equals_numpy_fancy_index_and_roundtrip():
+    cfg = W.TINY_SWAP
+    pool = W.random_pool_bytes(cfg)
+    src, dst = W.make_swap_lists(cfg)
+    assert len(set(src.tolist())) == cfg.n_move and not set(src.tolist()) & set(dst.tolist())
+    staging = oracle.pack_blocks(pool, src)
+    assert np.array_equal(staging, pool[src])          # library gather, list order
+    before = pool.copy()
+    oracle.unpack_blocks(pool, dst, staging)
+    assert np.array_equal(pool[dst], before[src])      # swapped-in context restored
+    untouched = np.setdiff1d(np.arange(cfg.pool_blocks), dst)
+    assert np.array_equal(pool[untouched], before[untouched])
+    # unpack to the same ids is the identity on the whole pool
+    pool2 = before.copy()
+    oracle.unpack_blocks(pool2, src, oracle.pack_blocks(pool2, src))
+    assert np.array_equal(pool2, before)
+
+
+def test_pack_order_duplicates_and_errors():
+    pool = np.arange(6 * 32, dtype=np.uint8).reshape(6, 32)
+    st = oracle.pack_blocks(pool, [4, 1, 4])           # duplicate sources are legal
+    assert np.array_equal(st, pool[[4, 1, 4]])
+    assert oracle.pack_blocks(pool, []).shape == (0, 32)
+    with pytest.raises(oracle.OracleError):
+        oracle.pack_blocks(pool, [6])
+    with pytest.raises(oracle.OracleError):
+        oracle.unpack_blocks(pool.copy(), [2, 2], st[:2])   # duplicate destinations
+    with pytest.raises(oracle.OracleError):
+        oracle.unpack_blocks(pool.copy(), [-1], st[:1])
