@@ -1,0 +1,182 @@
+/*
+ * infercept_hot.h - C ABI of the MI355X (gfx950) hot path of InferCept's intercept handling.
+ *
+ * Three operations, all on ONE layer's paged KV cache on ONE GPU:
+ *   paged_attn_mixed   attention for one iteration's mixed batch: decode sequences (one query
+ *                      row) and recomputation chunks (many query rows) read K/V through block tables
+ *   kv_pack_blocks     gather scattered cache blocks into a contiguous staging buffer  (swap-out)
+ *   kv_unpack_blocks   scatter a contiguous staging buffer back into cache blocks      (swap-in)
+ *
+ * General rules
+ *   - Every function returns IC_OK (0) or a negative IC_E* code.  Nothing aborts, throws or prints.
+ *     Arguments are validated before any kernel is launched: on error no device memory was written.
+ *   - "dev" pointers are device (HBM) addresses owned by the caller (for example a PyTorch tensor's
+ *     data_ptr) and must be 16-byte aligned.  "host" pointers are ordinary host memory; the library
+ *     copies what it needs before returning, so host arrays may be reused at once.
+ *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*, NULL = default stream);
+ *     the caller synchronises.  All calls that use one ic_pool must be issued on one stream, or be
+ *     ordered by the caller: the pool owns small descriptor buffers that successive calls reuse.
+ *   - One process, one device: the device current at the first GPU call of a pool is the pool's.
+ */
+#ifndef INFERCEPT_HOT_H
+#define INFERCEPT_HOT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  IC_OK = 0,
+  IC_ENULL = -1,        /* a required pointer is NULL                                   */
+  IC_EINVAL = -2,       /* a size, length or count is out of its legal range            */
+  IC_ERANGE = -3,       /* a block id lies outside [0, num_blocks)                      */
+  IC_ESIZE = -4,        /* a caller buffer (pool, staging, workspace, table) is too small */
+  IC_EALIGN = -5,       /* a device pointer is not 16-byte aligned                      */
+  IC_EDUP = -6,         /* duplicate destination id in kv_unpack_blocks                 */
+  IC_EUNSUPPORTED = -7, /* dtype, layout, head_dim, GQA ... not built                   */
+  IC_EOVERLAP = -8,     /* query-row ranges of two sequences overlap or leave [0,total) */
+  IC_EHIP = -9,         /* the HIP runtime reported an error                            */
+  IC_ENOMEM = -10       /* host allocation failed                                       */
+};
+
+/* Human-readable text for a return code (static storage, never NULL). */
+const char* ic_strerror(int code);
+
+/* ------------------------------------------------------------------------------------------
+ * The block pool (paper Section 3.1: the KV cache is virtual memory whose pages are physical
+ * blocks anywhere in GPU memory; Section 3.2 calls the per-token footprint M).
+ *
+ * layout 0:  pool[block][kv][head][slot][dim], kv = 0 for K and 1 for V, bf16.
+ *   One block = block_size tokens of ONE layer = block_size * M bytes, contiguous, so a swap
+ *   moves whole blocks; inside it each (kv, head) tile of block_size x head_dim is contiguous,
+ *   so attention reads it with full-width coalesced loads.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t num_blocks;   /* >= 1                                                          */
+  int32_t block_size;   /* tokens per block; 16 is the only size built                   */
+  int32_t num_heads;    /* query heads                                                   */
+  int32_t num_kv_heads; /* must equal num_heads (multi-head attention)                   */
+  int32_t head_dim;     /* 64, 128 or 256                                                */
+  int32_t dtype;        /* 0 = bf16                                                      */
+  int32_t layout;       /* 0 = the layout above                                          */
+} ic_pool_cfg;
+
+typedef struct ic_pool ic_pool; /* opaque; created by kv_pool_init, freed by kv_pool_destroy */
+
+/*
+ * Describe caller-owned pool memory to the library.  dev_pool_base: device, >= num_blocks *
+ * block bytes (IC_ESIZE otherwise), 16-byte aligned.  Allocates no KV memory and touches no GPU
+ * state; the pool's small descriptor buffers are created by the first GPU call that needs them.
+ */
+int kv_pool_init(const ic_pool_cfg* cfg, void* dev_pool_base, size_t pool_bytes, ic_pool** out);
+int kv_pool_destroy(ic_pool* pool); /* frees library-owned buffers; never the KV memory */
+
+/* block_size * 2 * num_kv_heads * head_dim * 2 bytes (K and V of one layer's block); 0 if pool is NULL. */
+size_t kv_block_bytes(const ic_pool* pool);
+
+/* ------------------------------------------------------------------------------------------
+ * Mixed-batch paged attention (Section 4.2: decoding and recomputation have complementary
+ * needs, so one iteration batches running requests' single decode tokens with one chunk of
+ * each resumed request's discarded context; Section 4.3: a partially recomputed request keeps
+ * its remaining tokens for later iterations).
+ *
+ * For sequence s and row i of its query span (0 <= i < q_len[s]) the row sits at absolute
+ * position p = ctx_len[s] - q_len[s] + i and
+ *      out[q_start[s] + i][h][:] = softmax_t( scale * q[q_start[s] + i][h] . K_t[h] ) V_t[h],  t = 0..p
+ * where token t lives in block block_tables[s][t / block_size], slot t % block_size.  The span's
+ * own K/V are already in the cache.  fp32 accumulation, bf16 result (round to nearest even).
+ * Slots at t >= ctx_len[s], table entries past ceil(ctx_len/block_size) and unreferenced blocks
+ * are never allowed to influence the result (they may hold NaN).
+ * ------------------------------------------------------------------------------------------ */
+enum {
+  IC_FLAG_TRUSTED = 1 /* skip the O(total blocks) host checks of ids and row ranges (timing loops) */
+};
+
+typedef struct {
+  int32_t num_seqs;           /* >= 1                                                          */
+  const int32_t* ctx_len;     /* host [num_seqs]  KV tokens visible, INCLUDING the span's own  */
+  const int32_t* q_len;       /* host [num_seqs]  1 = decode, >1 = recomputation chunk; 1..ctx_len */
+  const int32_t* q_start;     /* host [num_seqs]  first row of the sequence in packed q / out  */
+  const int32_t* block_tables;/* host [num_seqs][max_blocks_per_seq] row-major                 */
+  int32_t max_blocks_per_seq; /* row stride of block_tables                                    */
+  int32_t total_q_rows;       /* rows of q / out; every [q_start, q_start+q_len) inside, disjoint */
+  float scale;                /* softmax scale, 1/sqrt(head_dim) in the usual case             */
+  uint32_t flags;             /* IC_FLAG_*                                                     */
+} ic_batch_desc;
+
+/* Bytes of device workspace paged_attn_mixed needs for this batch (descriptor copy + split-KV
+ * partial results); 0 if an argument is NULL or the descriptor is invalid. */
+size_t paged_attn_mixed_workspace_bytes(const ic_pool* pool, const ic_batch_desc* desc);
+
+/*
+ * dev_q, dev_out: device bf16 [total_q_rows][num_heads][head_dim].  dev_workspace: device, at
+ * least paged_attn_mixed_workspace_bytes() (IC_ESIZE otherwise); its contents are scratch.
+ * Deterministic: the same inputs give the same bits on every call.
+ */
+int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q, void* dev_out,
+                     void* dev_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Host-only validation of a descriptor against a pool shape (what paged_attn_mixed checks when
+ * IC_FLAG_TRUSTED is clear).  Touches no GPU state. */
+int ic_check_batch(const ic_pool_cfg* cfg, const ic_batch_desc* desc);
+
+/* Launch plan knobs.  Partition sizes are in tokens and are rounded up to a multiple of 64;
+ * 0 keeps the built-in choice.  Smaller values force the split-KV path on short contexts. */
+typedef struct {
+  int32_t decode_part_tokens; /* keys per work item of a decode row                          */
+  int32_t span_part_tokens;   /* keys per work item of a span's query tile                   */
+  int32_t span_kernel;        /* 0 = built-in choice, 1 = row-by-row vector kernel, 2 = MFMA tiles */
+  int32_t reserved;
+} ic_tuning;
+int ic_pool_set_tuning(ic_pool* pool, const ic_tuning* tuning);
+
+/* What the planner would launch for this batch (host only; for tests and reports). */
+typedef struct {
+  int32_t decode_rows, span_rows;      /* query rows handled by each path                     */
+  int32_t row_items;                   /* work items of the vector (row) kernel, per head     */
+  int32_t tile_items;                  /* work items of the MFMA tile kernel, per head        */
+  int32_t partial_slots;               /* split-KV partial results, per head                  */
+  int32_t merge_rows;                  /* rows that need the merge pass                       */
+  int64_t table_entries;               /* block-table entries copied to the device            */
+} ic_plan_info;
+int ic_plan_query(const ic_pool* pool, const ic_batch_desc* desc, ic_plan_info* out);
+
+/* ------------------------------------------------------------------------------------------
+ * Swap of scattered blocks (Section 3.2, swap-based approach: a paged context is scattered over
+ * many discontinuous regions, and moving it with one launch per region is launch-bound;
+ * Section 4.1 moves it layer by layer, a bounded number of tokens per iteration).  One call moves
+ * one layer's K+V of the listed blocks in ONE launch; a chunk of the swap is a shorter id list.
+ *
+ *   kv_pack_blocks:    staging[i] <- pool[host_ids[i]]   i < n   (list order; duplicates allowed)
+ *   kv_unpack_blocks:  pool[host_ids[i]] <- staging[i]   i < n   (ids must be distinct: IC_EDUP)
+ * dev_staging: device, n * kv_block_bytes() bytes (IC_ESIZE if staging_bytes is smaller), must not
+ * overlap the pool.  n = 0 succeeds and does nothing.  Byte-exact.
+ * ------------------------------------------------------------------------------------------ */
+int kv_pack_blocks(ic_pool* pool, const int32_t* host_ids, int32_t n, void* dev_staging,
+                   size_t staging_bytes, void* hip_stream);
+int kv_unpack_blocks(ic_pool* pool, const int32_t* host_ids, int32_t n, const void* dev_staging,
+                     size_t staging_bytes, void* hip_stream);
+
+/* Host-only validation of an id list: range, and distinctness when require_distinct != 0. */
+int ic_check_ids(const ic_pool_cfg* cfg, const int32_t* host_ids, int32_t n, int require_distinct);
+
+/* ------------------------------------------------------------------------------------------
+ * Per-kernel timing with HIP events on the launch stream (for roofline reports).  Between
+ * ic_prof_begin and ic_prof_end every kernel the pool launches is bracketed by an event pair.
+ * ic_prof_end synchronises the recorded events and returns totals per kernel kind.
+ * ------------------------------------------------------------------------------------------ */
+enum { IC_K_ROW = 0, IC_K_TILE = 1, IC_K_MERGE = 2, IC_K_PACK = 3, IC_K_UNPACK = 4, IC_K_COUNT = 5 };
+typedef struct {
+  int32_t launches[IC_K_COUNT];
+  float total_ms[IC_K_COUNT];
+} ic_prof_stats;
+int ic_prof_begin(ic_pool* pool, int32_t max_launches);
+int ic_prof_end(ic_pool* pool, ic_prof_stats* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INFERCEPT_HOT_H */

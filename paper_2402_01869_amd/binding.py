@@ -1,0 +1,234 @@
+"""Thin ctypes binding of libinfercept_hot.so: argument marshalling only.
+
+Function names and argument order follow include/infercept_hot.h.  Every step of the hot path
+runs inside the library's HIP kernels; there is no fallback: if the library is not built, or an
+entry point fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libinfercept_hot.so")
+
+IC_OK = 0
+IC_ENULL, IC_EINVAL, IC_ERANGE, IC_ESIZE, IC_EALIGN = -1, -2, -3, -4, -5
+IC_EDUP, IC_EUNSUPPORTED, IC_EOVERLAP, IC_EHIP, IC_ENOMEM = -6, -7, -8, -9, -10
+IC_FLAG_TRUSTED = 1
+IC_K_ROW, IC_K_TILE, IC_K_MERGE, IC_K_PACK, IC_K_UNPACK, IC_K_COUNT = 0, 1, 2, 3, 4, 5
+KERNEL_NAMES = ("row", "tile", "merge", "pack", "unpack")
+
+EXPORTS = (
+    "ic_strerror", "kv_pool_init", "kv_pool_destroy", "kv_block_bytes",
+    "paged_attn_mixed_workspace_bytes", "paged_attn_mixed", "ic_check_batch", "ic_pool_set_tuning",
+    "ic_plan_query", "kv_pack_blocks", "kv_unpack_blocks", "ic_check_ids", "ic_prof_begin",
+    "ic_prof_end",
+)
+
+
+class PoolCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("num_blocks", "block_size", "num_heads", "num_kv_heads", "head_dim", "dtype", "layout")]
+
+
+class BatchDesc(C.Structure):
+    _fields_ = [("num_seqs", C.c_int32),
+                ("ctx_len", C.POINTER(C.c_int32)),
+                ("q_len", C.POINTER(C.c_int32)),
+                ("q_start", C.POINTER(C.c_int32)),
+                ("block_tables", C.POINTER(C.c_int32)),
+                ("max_blocks_per_seq", C.c_int32),
+                ("total_q_rows", C.c_int32),
+                ("scale", C.c_float),
+                ("flags", C.c_uint32)]
+
+
+class Tuning(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("decode_part_tokens", "span_part_tokens", "span_kernel", "reserved")]
+
+
+class PlanInfo(C.Structure):
+    _fields_ = [("decode_rows", C.c_int32), ("span_rows", C.c_int32), ("row_items", C.c_int32),
+                ("tile_items", C.c_int32), ("partial_slots", C.c_int32), ("merge_rows", C.c_int32),
+                ("table_entries", C.c_int64)]
+
+
+class ProfStats(C.Structure):
+    _fields_ = [("launches", C.c_int32 * IC_K_COUNT), ("total_ms", C.c_float * IC_K_COUNT)]
+
+
+class InferceptError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library; fails loudly if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2402_01869_amd.build` "
+                              "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
+        L.ic_strerror.argtypes, L.ic_strerror.restype = [C.c_int], C.c_char_p
+        L.kv_pool_init.argtypes = [C.POINTER(PoolCfg), vp, C.c_size_t, C.POINTER(vp)]
+        L.kv_pool_destroy.argtypes = [vp]
+        L.kv_block_bytes.argtypes, L.kv_block_bytes.restype = [vp], C.c_size_t
+        L.paged_attn_mixed_workspace_bytes.argtypes = [vp, C.POINTER(BatchDesc)]
+        L.paged_attn_mixed_workspace_bytes.restype = C.c_size_t
+        L.paged_attn_mixed.argtypes = [vp, C.POINTER(BatchDesc), vp, vp, vp, C.c_size_t, vp]
+        L.ic_check_batch.argtypes = [C.POINTER(PoolCfg), C.POINTER(BatchDesc)]
+        L.ic_pool_set_tuning.argtypes = [vp, C.POINTER(Tuning)]
+        L.ic_plan_query.argtypes = [vp, C.POINTER(BatchDesc), C.POINTER(PlanInfo)]
+        L.kv_pack_blocks.argtypes = [vp, i32p, C.c_int32, vp, C.c_size_t, vp]
+        L.kv_unpack_blocks.argtypes = [vp, i32p, C.c_int32, vp, C.c_size_t, vp]
+        L.ic_check_ids.argtypes = [C.POINTER(PoolCfg), i32p, C.c_int32, C.c_int]
+        L.ic_prof_begin.argtypes = [vp, C.c_int32]
+        L.ic_prof_end.argtypes = [vp, C.POINTER(ProfStats)]
+        for name in EXPORTS:
+            if name not in ("ic_strerror", "kv_block_bytes", "paged_attn_mixed_workspace_bytes"):
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().ic_strerror(int(code)).decode()
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def make_cfg(num_blocks, num_heads, head_dim, block_size=16, num_kv_heads=None, dtype=0, layout=0) -> PoolCfg:
+    return PoolCfg(int(num_blocks), int(block_size), int(num_heads),
+                   int(num_heads if num_kv_heads is None else num_kv_heads), int(head_dim), dtype, layout)
+
+
+class HostDesc:
+    """Keeps the numpy arrays of a batch descriptor alive next to the ctypes struct."""
+
+    def __init__(self, ctx_len, q_len, q_start, block_tables, scale, total_q_rows=None, flags=0):
+        self.ctx_len, self.q_len, self.q_start = _i32(ctx_len), _i32(q_len), _i32(q_start)
+        self.block_tables = _i32(block_tables)
+        if self.block_tables.ndim != 2:
+            raise ValueError("block_tables must be [num_seqs][max_blocks_per_seq]")
+        rows = int(self.q_len.sum()) if total_q_rows is None else int(total_q_rows)
+        self.struct = BatchDesc(int(self.ctx_len.shape[0]), _ptr(self.ctx_len), _ptr(self.q_len),
+                                _ptr(self.q_start), _ptr(self.block_tables),
+                                int(self.block_tables.shape[1]), rows, float(scale), int(flags))
+
+    @classmethod
+    def from_batch(cls, batch, flags=0):
+        return cls(batch.ctx_len, batch.q_len, batch.q_start, batch.block_tables, batch.scale,
+                   batch.total_q_rows, flags)
+
+
+def check_batch(cfg: PoolCfg, desc: HostDesc) -> int:
+    return int(lib().ic_check_batch(C.byref(cfg), C.byref(desc.struct)))
+
+
+def check_ids(cfg: PoolCfg, ids, require_distinct: bool) -> int:
+    ids = _i32(ids)
+    return int(lib().ic_check_ids(C.byref(cfg), _ptr(ids), int(ids.shape[0]), int(require_distinct)))
+
+
+class KvPool:
+    """kv_pool_init / kv_pool_destroy wrapper.  `dev_ptr` is caller-owned device memory."""
+
+    def __init__(self, cfg: PoolCfg, dev_ptr: int, pool_bytes: int):
+        self.cfg = cfg
+        self._h = C.c_void_p()
+        rc = lib().kv_pool_init(C.byref(cfg), C.c_void_p(dev_ptr), int(pool_bytes), C.byref(self._h))
+        if rc != IC_OK:
+            raise InferceptError(rc, "kv_pool_init")
+
+    @classmethod
+    def from_tensor(cls, pool_t, num_heads, head_dim, block_size=16):
+        """pool_t: a contiguous torch device tensor holding [blocks][2][H][B][D] bf16."""
+        nbytes = pool_t.numel() * pool_t.element_size()
+        bb = block_size * 2 * num_heads * head_dim * 2
+        obj = cls(make_cfg(nbytes // bb, num_heads, head_dim, block_size), pool_t.data_ptr(), nbytes)
+        obj._keep = pool_t
+        return obj
+
+    def close(self):
+        if self._h:
+            lib().kv_pool_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def block_bytes(self) -> int:
+        return int(lib().kv_block_bytes(self._h))
+
+    def set_tuning(self, decode_part_tokens=0, span_part_tokens=0, span_kernel=0):
+        t = Tuning(int(decode_part_tokens), int(span_part_tokens), int(span_kernel), 0)
+        rc = lib().ic_pool_set_tuning(self._h, C.byref(t))
+        if rc != IC_OK:
+            raise InferceptError(rc, "ic_pool_set_tuning")
+
+    def plan_query(self, desc: HostDesc) -> dict:
+        info = PlanInfo()
+        rc = lib().ic_plan_query(self._h, C.byref(desc.struct), C.byref(info))
+        if rc != IC_OK:
+            raise InferceptError(rc, "ic_plan_query")
+        return {n: int(getattr(info, n)) for n, _ in PlanInfo._fields_}
+
+    def workspace_bytes(self, desc: HostDesc) -> int:
+        return int(lib().paged_attn_mixed_workspace_bytes(self._h, C.byref(desc.struct)))
+
+    def paged_attn_mixed(self, desc: HostDesc, q_ptr: int, out_ptr: int, ws_ptr: int, ws_bytes: int,
+                         stream: int = 0, check: bool = True) -> int:
+        rc = lib().paged_attn_mixed(self._h, C.byref(desc.struct), C.c_void_p(q_ptr), C.c_void_p(out_ptr),
+                                    C.c_void_p(ws_ptr), int(ws_bytes), C.c_void_p(stream))
+        if check and rc != IC_OK:
+            raise InferceptError(rc, "paged_attn_mixed")
+        return int(rc)
+
+    def kv_pack_blocks(self, ids, staging_ptr: int, staging_bytes: int, stream: int = 0, check: bool = True) -> int:
+        ids = _i32(ids)
+        rc = lib().kv_pack_blocks(self._h, _ptr(ids), int(ids.shape[0]), C.c_void_p(staging_ptr),
+                                  int(staging_bytes), C.c_void_p(stream))
+        if check and rc != IC_OK:
+            raise InferceptError(rc, "kv_pack_blocks")
+        return int(rc)
+
+    def kv_unpack_blocks(self, ids, staging_ptr: int, staging_bytes: int, stream: int = 0, check: bool = True) -> int:
+        ids = _i32(ids)
+        rc = lib().kv_unpack_blocks(self._h, _ptr(ids), int(ids.shape[0]), C.c_void_p(staging_ptr),
+                                    int(staging_bytes), C.c_void_p(stream))
+        if check and rc != IC_OK:
+            raise InferceptError(rc, "kv_unpack_blocks")
+        return int(rc)
+
+    def prof_begin(self, max_launches: int = 4096):
+        rc = lib().ic_prof_begin(self._h, int(max_launches))
+        if rc != IC_OK:
+            raise InferceptError(rc, "ic_prof_begin")
+
+    def prof_end(self) -> dict:
+        st = ProfStats()
+        rc = lib().ic_prof_end(self._h, C.byref(st))
+        if rc != IC_OK:
+            raise InferceptError(rc, "ic_prof_end")
+        return {KERNEL_NAMES[k]: {"launches": int(st.launches[k]), "total_ms": float(st.total_ms[k])}
+                for k in range(IC_K_COUNT)}

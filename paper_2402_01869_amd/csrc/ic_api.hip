@@ -1,0 +1,518 @@
+// C ABI, host-side validation and launch planning for the intercept hot path.
+// See include/infercept_hot.h for the contract of every entry point.
+#include "../../include/infercept_hot.h"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "ic_internal.h"
+
+using namespace ic;
+
+namespace {
+
+constexpr int kStagingSlots = 4;       // pinned host buffers cycled by successive calls
+constexpr int kDefaultRowPart = 256;   // keys per decode work item
+constexpr int kDefaultSpanPart = 4096; // keys per span-tile work item
+constexpr int kTileRows = 128;         // query rows per MFMA tile work item
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct StagingSlot {
+  void* host = nullptr;
+  size_t cap = 0;
+  hipEvent_t ev = nullptr;
+  bool pending = false;
+};
+
+struct ProfState {
+  bool on = false;
+  std::vector<hipEvent_t> ev;       // pairs
+  std::vector<int> kind;            // per pair
+  int used = 0;                     // pairs recorded
+};
+
+}  // namespace
+
+struct ic_pool {
+  ic_pool_cfg cfg;
+  char* base;
+  size_t bytes;
+  size_t block_bytes;
+  ic_tuning tune;
+  // library-owned runtime state (created lazily by the first GPU call)
+  StagingSlot slots[kStagingSlots];
+  int next_slot;
+  int32_t* dev_ids;
+  size_t dev_ids_cap;
+  ProfState prof;
+};
+
+namespace {
+
+int check_cfg(const ic_pool_cfg* c) {
+  if (!c) return IC_ENULL;
+  if (c->num_blocks < 1 || c->num_heads < 1 || c->num_kv_heads < 1 || c->head_dim < 1 ||
+      c->block_size < 1)
+    return IC_EINVAL;
+  if (c->dtype != 0 || c->layout != 0) return IC_EUNSUPPORTED;
+  if (c->block_size != kBlockSize) return IC_EUNSUPPORTED;
+  if (c->num_kv_heads != c->num_heads) return IC_EUNSUPPORTED;
+  if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return IC_EUNSUPPORTED;
+  if (c->num_heads > 4096) return IC_EINVAL;
+  return IC_OK;
+}
+
+size_t cfg_block_bytes(const ic_pool_cfg& c) {
+  return (size_t)c.block_size * 2 * c.num_kv_heads * c.head_dim * 2;
+}
+
+// Structural checks (always done) and content checks (skipped when trusted).
+int check_batch(const ic_pool_cfg& cfg, const ic_batch_desc* d, bool trusted) {
+  if (!d) return IC_ENULL;
+  if (!d->ctx_len || !d->q_len || !d->q_start || !d->block_tables) return IC_ENULL;
+  if (d->num_seqs < 1 || d->max_blocks_per_seq < 1 || d->total_q_rows < 1) return IC_EINVAL;
+  if (!(d->scale == d->scale) || d->scale < 0.f || d->scale > 3.0e38f) return IC_EINVAL;
+  int64_t rows = 0;
+  for (int s = 0; s < d->num_seqs; ++s) {
+    const int32_t c = d->ctx_len[s], n = d->q_len[s];
+    if (c < 1 || n < 1 || n > c) return IC_EINVAL;
+    if ((c + kBlockSize - 1) / kBlockSize > d->max_blocks_per_seq) return IC_ESIZE;
+    const int64_t r0 = d->q_start[s];
+    if (r0 < 0 || r0 + n > d->total_q_rows) return IC_EOVERLAP;
+    rows += n;
+  }
+  if (rows > d->total_q_rows) return IC_EOVERLAP;
+  if (trusted) return IC_OK;
+  std::vector<uint8_t> taken((size_t)d->total_q_rows, 0);
+  for (int s = 0; s < d->num_seqs; ++s) {
+    for (int32_t r = d->q_start[s]; r < d->q_start[s] + d->q_len[s]; ++r) {
+      if (taken[r]) return IC_EOVERLAP;
+      taken[r] = 1;
+    }
+    const int nb = (d->ctx_len[s] + kBlockSize - 1) / kBlockSize;
+    const int32_t* row = d->block_tables + (int64_t)s * d->max_blocks_per_seq;
+    for (int j = 0; j < nb; ++j)
+      if (row[j] < 0 || row[j] >= cfg.num_blocks) return IC_ERANGE;
+  }
+  return IC_OK;
+}
+
+int check_ids(const ic_pool_cfg& cfg, const int32_t* ids, int32_t n, bool distinct) {
+  if (n < 0) return IC_EINVAL;
+  if (n == 0) return IC_OK;
+  if (!ids) return IC_ENULL;
+  for (int32_t i = 0; i < n; ++i)
+    if (ids[i] < 0 || ids[i] >= cfg.num_blocks) return IC_ERANGE;
+  if (distinct) {
+    std::vector<uint8_t> seen((size_t)cfg.num_blocks, 0);
+    for (int32_t i = 0; i < n; ++i) {
+      if (seen[ids[i]]) return IC_EDUP;
+      seen[ids[i]] = 1;
+    }
+  }
+  return IC_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// Launch plan.  Sizes only (plan_sizes) or the filled descriptor image (plan_fill).
+// Device image layout (all sections 256-byte aligned, in this order):
+//   bt_off[num_seqs] | bt_flat[table_entries] | row_items | tile_items | merge_items
+// followed in the workspace by part_o[slots][H][D] and part_ml[slots][H][2].
+// ---------------------------------------------------------------------------------------
+struct PlanSizes {
+  ic_plan_info info;
+  int row_part, span_part;
+  bool spans_as_rows;
+  size_t off_bt_off, off_bt_flat, off_row, off_tile, off_merge, image_bytes;
+  size_t off_part_o, off_part_ml, total_bytes;
+};
+
+int round64(int x) { return (x + 63) / 64 * 64; }
+
+void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
+  std::memset(&ps, 0, sizeof ps);
+  const ic_tuning& t = pool->tune;
+  ps.row_part = t.decode_part_tokens > 0 ? round64(t.decode_part_tokens) : kDefaultRowPart;
+  ps.row_part = std::min(ps.row_part, kMaxRowPart);
+  ps.span_part = t.span_part_tokens > 0 ? round64(t.span_part_tokens) : kDefaultSpanPart;
+  ps.spans_as_rows = (t.span_kernel != 2);  // MFMA tiles only when asked, until they are the default
+  ic_plan_info& in = ps.info;
+  for (int s = 0; s < d->num_seqs; ++s) {
+    const int c = d->ctx_len[s], n = d->q_len[s];
+    in.table_entries += (c + kBlockSize - 1) / kBlockSize;
+    if (n == 1 || ps.spans_as_rows) {
+      if (n == 1) in.decode_rows += 1; else in.span_rows += n;
+      for (int i = 0; i < n; ++i) {
+        const int klen = c - n + i + 1;
+        const int parts = (klen + ps.row_part - 1) / ps.row_part;
+        in.row_items += parts;
+        if (parts > 1) { in.partial_slots += parts; in.merge_rows += 1; }
+      }
+    } else {
+      in.span_rows += n;
+      for (int r0 = 0; r0 < n; r0 += kTileRows) {
+        const int nr = std::min(kTileRows, n - r0);
+        const int klen = c - n + r0 + nr;  // keys visible to the tile's last row
+        const int parts = (klen + ps.span_part - 1) / ps.span_part;
+        in.tile_items += parts;
+        if (parts > 1) { in.partial_slots += parts * nr; in.merge_rows += nr; }
+      }
+    }
+  }
+  const int H = pool->cfg.num_heads, D = pool->cfg.head_dim;
+  size_t o = 0;
+  ps.off_bt_off = o;  o = align_up(o + sizeof(int32_t) * (size_t)d->num_seqs, 256);
+  ps.off_bt_flat = o; o = align_up(o + sizeof(int32_t) * (size_t)in.table_entries, 256);
+  ps.off_row = o;     o = align_up(o + sizeof(RowItem) * (size_t)in.row_items, 256);
+  ps.off_tile = o;    o = align_up(o + sizeof(TileItem) * (size_t)in.tile_items, 256);
+  ps.off_merge = o;   o = align_up(o + sizeof(MergeItem) * (size_t)in.merge_rows, 256);
+  ps.image_bytes = o;
+  ps.off_part_o = o;  o = align_up(o + sizeof(float) * (size_t)in.partial_slots * H * D, 256);
+  ps.off_part_ml = o; o = align_up(o + sizeof(float) * (size_t)in.partial_slots * H * 2, 256);
+  ps.total_bytes = o;
+}
+
+void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
+  int32_t* bt_off = (int32_t*)(img + ps.off_bt_off);
+  int32_t* bt_flat = (int32_t*)(img + ps.off_bt_flat);
+  RowItem* rows = (RowItem*)(img + ps.off_row);
+  TileItem* tiles = (TileItem*)(img + ps.off_tile);
+  MergeItem* merges = (MergeItem*)(img + ps.off_merge);
+  int64_t nbt = 0;
+  int nrow = 0, ntile = 0, nmerge = 0, slot = 0;
+  for (int s = 0; s < d->num_seqs; ++s) {
+    const int c = d->ctx_len[s], n = d->q_len[s];
+    const int nb = (c + kBlockSize - 1) / kBlockSize;
+    bt_off[s] = (int32_t)nbt;
+    std::memcpy(bt_flat + nbt, d->block_tables + (int64_t)s * d->max_blocks_per_seq,
+                sizeof(int32_t) * (size_t)nb);
+    nbt += nb;
+    if (n == 1 || ps.spans_as_rows) {
+      for (int i = 0; i < n; ++i) {
+        const int klen = c - n + i + 1;
+        const int parts = (klen + ps.row_part - 1) / ps.row_part;
+        const int qrow = d->q_start[s] + i;
+        if (parts > 1) merges[nmerge++] = MergeItem{qrow, slot, parts, 0};
+        for (int k = 0; k < parts; ++k) {
+          RowItem& it = rows[nrow++];
+          it.seq = s;
+          it.qrow = qrow;
+          it.k_begin = k * ps.row_part;
+          it.k_end = std::min(klen, (k + 1) * ps.row_part);
+          it.slot = parts > 1 ? slot++ : -1;
+          it.pad[0] = it.pad[1] = it.pad[2] = 0;
+        }
+      }
+    } else {
+      for (int r0 = 0; r0 < n; r0 += kTileRows) {
+        const int nr = std::min(kTileRows, n - r0);
+        const int pos0 = c - n + r0;
+        const int klen = pos0 + nr;
+        const int parts = (klen + ps.span_part - 1) / ps.span_part;
+        const int slot0 = parts > 1 ? slot : -1;
+        if (parts > 1) {
+          for (int r = 0; r < nr; ++r)
+            merges[nmerge++] = MergeItem{d->q_start[s] + r0 + r, slot + r * parts, parts, 0};
+          slot += parts * nr;
+        }
+        for (int k = 0; k < parts; ++k) {
+          TileItem& it = tiles[ntile++];
+          it.seq = s;
+          it.qrow0 = d->q_start[s] + r0;
+          it.n_rows = nr;
+          it.pos0 = pos0;
+          it.k_begin = k * ps.span_part;
+          it.k_end = std::min(klen, (k + 1) * ps.span_part);
+          it.slot0 = parts > 1 ? slot0 + k : -1;
+          it.nparts = parts;
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Runtime helpers
+// ---------------------------------------------------------------------------------------
+int acquire_slot(ic_pool* pool, size_t bytes, StagingSlot** out) {
+  StagingSlot& s = pool->slots[pool->next_slot];
+  pool->next_slot = (pool->next_slot + 1) % kStagingSlots;
+  if (s.pending) {
+    if (hipEventSynchronize(s.ev) != hipSuccess) return IC_EHIP;
+    s.pending = false;
+  }
+  if (!s.ev && hipEventCreateWithFlags(&s.ev, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
+  if (s.cap < bytes) {
+    if (s.host) (void)hipHostFree(s.host);
+    s.host = nullptr;
+    s.cap = 0;
+    const size_t cap = align_up(std::max(bytes, (size_t)1 << 16), 4096);
+    if (hipHostMalloc(&s.host, cap, hipHostMallocDefault) != hipSuccess) return IC_EHIP;
+    s.cap = cap;
+  }
+  *out = &s;
+  return IC_OK;
+}
+
+struct ProfScope {
+  ic_pool* pool;
+  hipStream_t st;
+  int idx;
+  ProfScope(ic_pool* p, int kind, hipStream_t s) : pool(p), st(s), idx(-1) {
+    ProfState& pr = p->prof;
+    if (pr.on && (size_t)(pr.used + 1) * 2 <= pr.ev.size()) {
+      idx = pr.used++;
+      pr.kind[idx] = kind;
+      (void)hipEventRecord(pr.ev[2 * idx], st);
+    }
+  }
+  ~ProfScope() {
+    if (idx >= 0) (void)hipEventRecord(pool->prof.ev[2 * idx + 1], st);
+  }
+};
+
+bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+}  // namespace
+
+// =========================================================================================
+extern "C" {
+
+const char* ic_strerror(int code) {
+  switch (code) {
+    case IC_OK: return "ok";
+    case IC_ENULL: return "null pointer argument";
+    case IC_EINVAL: return "size, length or count out of range";
+    case IC_ERANGE: return "block id outside the pool";
+    case IC_ESIZE: return "caller buffer too small";
+    case IC_EALIGN: return "device pointer not 16-byte aligned";
+    case IC_EDUP: return "duplicate destination block id";
+    case IC_EUNSUPPORTED: return "configuration not supported by this build";
+    case IC_EOVERLAP: return "query-row ranges overlap or leave the packed array";
+    case IC_EHIP: return "HIP runtime error";
+    case IC_ENOMEM: return "host allocation failed";
+    default: return "unknown error code";
+  }
+}
+
+int kv_pool_init(const ic_pool_cfg* cfg, void* dev_pool_base, size_t pool_bytes, ic_pool** out) {
+  if (!cfg || !dev_pool_base || !out) return IC_ENULL;
+  const int rc = check_cfg(cfg);
+  if (rc != IC_OK) return rc;
+  if (misaligned(dev_pool_base)) return IC_EALIGN;
+  const size_t bb = cfg_block_bytes(*cfg);
+  if (pool_bytes / bb < (size_t)cfg->num_blocks) return IC_ESIZE;
+  ic_pool* p = new (std::nothrow) ic_pool();
+  if (!p) return IC_ENOMEM;
+  p->cfg = *cfg;
+  p->base = (char*)dev_pool_base;
+  p->bytes = pool_bytes;
+  p->block_bytes = bb;
+  std::memset(&p->tune, 0, sizeof p->tune);
+  p->next_slot = 0;
+  p->dev_ids = nullptr;
+  p->dev_ids_cap = 0;
+  *out = p;
+  return IC_OK;
+}
+
+int kv_pool_destroy(ic_pool* pool) {
+  if (!pool) return IC_ENULL;
+  int rc = IC_OK;
+  for (StagingSlot& s : pool->slots) {
+    if (s.pending && hipEventSynchronize(s.ev) != hipSuccess) rc = IC_EHIP;
+    if (s.ev) (void)hipEventDestroy(s.ev);
+    if (s.host) (void)hipHostFree(s.host);
+  }
+  for (hipEvent_t e : pool->prof.ev) (void)hipEventDestroy(e);
+  if (pool->dev_ids) (void)hipFree(pool->dev_ids);
+  delete pool;
+  return rc;
+}
+
+size_t kv_block_bytes(const ic_pool* pool) { return pool ? pool->block_bytes : 0; }
+
+int ic_check_batch(const ic_pool_cfg* cfg, const ic_batch_desc* desc) {
+  const int rc = check_cfg(cfg);
+  if (rc != IC_OK) return rc;
+  return check_batch(*cfg, desc, false);
+}
+
+int ic_check_ids(const ic_pool_cfg* cfg, const int32_t* host_ids, int32_t n, int require_distinct) {
+  const int rc = check_cfg(cfg);
+  if (rc != IC_OK) return rc;
+  return check_ids(*cfg, host_ids, n, require_distinct != 0);
+}
+
+int ic_pool_set_tuning(ic_pool* pool, const ic_tuning* tuning) {
+  if (!pool || !tuning) return IC_ENULL;
+  if (tuning->decode_part_tokens < 0 || tuning->span_part_tokens < 0 || tuning->span_kernel < 0 ||
+      tuning->span_kernel > 2)
+    return IC_EINVAL;
+  pool->tune = *tuning;
+  return IC_OK;
+}
+
+int ic_plan_query(const ic_pool* pool, const ic_batch_desc* desc, ic_plan_info* out) {
+  if (!pool || !desc || !out) return IC_ENULL;
+  const int rc = check_batch(pool->cfg, desc, true);
+  if (rc != IC_OK) return rc;
+  PlanSizes ps;
+  plan_sizes(pool, desc, ps);
+  *out = ps.info;
+  return IC_OK;
+}
+
+size_t paged_attn_mixed_workspace_bytes(const ic_pool* pool, const ic_batch_desc* desc) {
+  if (!pool || !desc) return 0;
+  if (check_batch(pool->cfg, desc, true) != IC_OK) return 0;
+  PlanSizes ps;
+  plan_sizes(pool, desc, ps);
+  return ps.total_bytes;
+}
+
+int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q, void* dev_out,
+                     void* dev_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!pool || !desc || !dev_q || !dev_out || !dev_workspace) return IC_ENULL;
+  int rc = check_batch(pool->cfg, desc, (desc->flags & IC_FLAG_TRUSTED) != 0);
+  if (rc != IC_OK) return rc;
+  if (misaligned(dev_q) || misaligned(dev_out) || ((uintptr_t)dev_workspace & 255u)) return IC_EALIGN;
+  PlanSizes ps;
+  plan_sizes(pool, desc, ps);
+  if (workspace_bytes < ps.total_bytes) return IC_ESIZE;
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  StagingSlot* slot = nullptr;
+  rc = acquire_slot(pool, ps.image_bytes, &slot);
+  if (rc != IC_OK) return rc;
+  plan_fill(desc, ps, (char*)slot->host);
+  char* ws = (char*)dev_workspace;
+  if (hipMemcpyAsync(ws, slot->host, ps.image_bytes, hipMemcpyHostToDevice, st) != hipSuccess)
+    return IC_EHIP;
+  if (hipEventRecord(slot->ev, st) != hipSuccess) return IC_EHIP;
+  slot->pending = true;
+
+  AttnParams p;
+  p.pool = (const uint16_t*)pool->base;
+  p.q = (const uint16_t*)dev_q;
+  p.out = (uint16_t*)dev_out;
+  p.bt_off = (const int32_t*)(ws + ps.off_bt_off);
+  p.bt_flat = (const int32_t*)(ws + ps.off_bt_flat);
+  p.row_items = (const RowItem*)(ws + ps.off_row);
+  p.tile_items = (const TileItem*)(ws + ps.off_tile);
+  p.merge_items = (const MergeItem*)(ws + ps.off_merge);
+  p.part_o = (float*)(ws + ps.off_part_o);
+  p.part_ml = (float*)(ws + ps.off_part_ml);
+  p.num_heads = pool->cfg.num_heads;
+  p.n_row_items = ps.info.row_items;
+  p.n_tile_items = ps.info.tile_items;
+  p.n_merge_items = ps.info.merge_rows;
+  p.scale_log2e = desc->scale * 1.4426950408889634f;
+
+  const int D = pool->cfg.head_dim;
+  if (p.n_tile_items > 0) {
+    ProfScope ps_(pool, IC_K_TILE, st);
+    if (launch_tile_kernel(p, D, st) != hipSuccess) return IC_EHIP;
+  }
+  if (p.n_row_items > 0) {
+    ProfScope ps_(pool, IC_K_ROW, st);
+    if (launch_row_kernel(p, D, st) != hipSuccess) return IC_EHIP;
+  }
+  if (p.n_merge_items > 0) {
+    ProfScope ps_(pool, IC_K_MERGE, st);
+    if (launch_merge_kernel(p, D, st) != hipSuccess) return IC_EHIP;
+  }
+  return IC_OK;
+}
+
+static int swap_common(ic_pool* pool, const int32_t* host_ids, int32_t n, const void* dev_staging,
+                       size_t staging_bytes, void* hip_stream, bool pack) {
+  if (!pool) return IC_ENULL;
+  if (n < 0) return IC_EINVAL;
+  if (n == 0) return IC_OK;
+  if (!host_ids || !dev_staging) return IC_ENULL;
+  int rc = check_ids(pool->cfg, host_ids, n, !pack);
+  if (rc != IC_OK) return rc;
+  if (misaligned(dev_staging)) return IC_EALIGN;
+  if (staging_bytes / pool->block_bytes < (size_t)n) return IC_ESIZE;
+  {  // staging must not overlap the pool
+    const char* s0 = (const char*)dev_staging;
+    const char* s1 = s0 + (size_t)n * pool->block_bytes;
+    if (s0 < pool->base + pool->bytes && pool->base < s1) return IC_EINVAL;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t bytes = sizeof(int32_t) * (size_t)n;
+  if (pool->dev_ids_cap < bytes) {
+    // Growing the id buffer: earlier launches may still read the old one.
+    if (pool->dev_ids) {
+      if (hipDeviceSynchronize() != hipSuccess) return IC_EHIP;
+      (void)hipFree(pool->dev_ids);
+      pool->dev_ids = nullptr;
+      pool->dev_ids_cap = 0;
+    }
+    const size_t cap = align_up(std::max(bytes, (size_t)1 << 16), 4096);
+    if (hipMalloc((void**)&pool->dev_ids, cap) != hipSuccess) return IC_EHIP;
+    pool->dev_ids_cap = cap;
+  }
+  StagingSlot* slot = nullptr;
+  rc = acquire_slot(pool, bytes, &slot);
+  if (rc != IC_OK) return rc;
+  std::memcpy(slot->host, host_ids, bytes);
+  if (hipMemcpyAsync(pool->dev_ids, slot->host, bytes, hipMemcpyHostToDevice, st) != hipSuccess)
+    return IC_EHIP;
+  if (hipEventRecord(slot->ev, st) != hipSuccess) return IC_EHIP;
+  slot->pending = true;
+  hipError_t e;
+  {
+    ProfScope ps_(pool, pack ? IC_K_PACK : IC_K_UNPACK, st);
+    e = pack ? launch_pack(pool->base, (void*)dev_staging, pool->dev_ids, n, pool->block_bytes, st)
+             : launch_unpack(pool->base, dev_staging, pool->dev_ids, n, pool->block_bytes, st);
+  }
+  return e == hipSuccess ? IC_OK : IC_EHIP;
+}
+
+int kv_pack_blocks(ic_pool* pool, const int32_t* host_ids, int32_t n, void* dev_staging,
+                   size_t staging_bytes, void* hip_stream) {
+  return swap_common(pool, host_ids, n, dev_staging, staging_bytes, hip_stream, true);
+}
+
+int kv_unpack_blocks(ic_pool* pool, const int32_t* host_ids, int32_t n, const void* dev_staging,
+                     size_t staging_bytes, void* hip_stream) {
+  return swap_common(pool, host_ids, n, dev_staging, staging_bytes, hip_stream, false);
+}
+
+int ic_prof_begin(ic_pool* pool, int32_t max_launches) {
+  if (!pool) return IC_ENULL;
+  if (max_launches < 1 || max_launches > (1 << 20)) return IC_EINVAL;
+  ProfState& pr = pool->prof;
+  while (pr.ev.size() < (size_t)max_launches * 2) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return IC_EHIP;
+    pr.ev.push_back(e);
+  }
+  pr.kind.assign(pr.ev.size() / 2, 0);
+  pr.used = 0;
+  pr.on = true;
+  return IC_OK;
+}
+
+int ic_prof_end(ic_pool* pool, ic_prof_stats* out) {
+  if (!pool || !out) return IC_ENULL;
+  ProfState& pr = pool->prof;
+  std::memset(out, 0, sizeof *out);
+  pr.on = false;
+  for (int i = 0; i < pr.used; ++i) {
+    if (hipEventSynchronize(pr.ev[2 * i + 1]) != hipSuccess) return IC_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, pr.ev[2 * i], pr.ev[2 * i + 1]) != hipSuccess) return IC_EHIP;
+    out->launches[pr.kind[i]] += 1;
+    out->total_ms[pr.kind[i]] += ms;
+  }
+  pr.used = 0;
+  return IC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+// Internal declarations shared by the host-side planner and the gfx950 kernels.
+// Nothing here is part of the C ABI (include/infercept_hot.h is).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ic {
+
+constexpr int kBlockSize = 16;  // tokens per cache block (the only size built)
+constexpr int kRowWaves = 4;    // waves per workgroup of the row kernel
+constexpr int kMaxRowPart = 4096;  // keys per row-kernel work item: 64 block ids per wave
+
+// One work item of the row kernel: one query row against keys [k_begin, k_end) of its sequence,
+// for every head (the head is a grid dimension).  32 bytes so a wave reads it with scalar loads.
+struct RowItem {
+  int32_t seq;      // index into bt_off
+  int32_t qrow;     // row in packed q / out
+  int32_t k_begin;  // first key, multiple of 16
+  int32_t k_end;    // one past the last visible key of this item
+  int32_t slot;     // partial-result slot, or -1: the item is the whole row, write bf16 out
+  int32_t pad[3];
+};
+
+// One work item of the MFMA tile kernel: up to 128 consecutive rows of one span against keys
+// [k_begin, k_end) (k_end is a bound for the LAST row; earlier rows see fewer keys).
+struct TileItem {
+  int32_t seq;
+  int32_t qrow0;    // first row of the tile in packed q / out
+  int32_t n_rows;   // rows in this tile (<= tile height)
+  int32_t pos0;     // absolute position of the tile's first row: it sees keys 0..pos0
+  int32_t k_begin;  // first key of this partition, multiple of 64
+  int32_t k_end;    // one past the last key of this partition (<= pos0 + n_rows)
+  int32_t slot0;    // partial slot of (row 0, this partition) or -1 for direct output
+  int32_t nparts;   // partitions of this tile: slot(row r) = slot0 + r * nparts
+};
+
+// One row whose partial results must be merged.
+struct MergeItem {
+  int32_t qrow;
+  int32_t slot0;
+  int32_t nparts;
+  int32_t pad;
+};
+
+struct AttnParams {
+  const uint16_t* pool;
+  const uint16_t* q;
+  uint16_t* out;
+  const int32_t* bt_off;   // [num_seqs] offset of each sequence's ids in bt_flat
+  const int32_t* bt_flat;  // compacted block tables
+  const RowItem* row_items;
+  const TileItem* tile_items;
+  const MergeItem* merge_items;
+  float* part_o;           // [slots][H][D] unnormalised partial outputs
+  float* part_ml;          // [slots][H][2] (running max in log2 units, normaliser)
+  int32_t num_heads;
+  int32_t n_row_items;
+  int32_t n_tile_items;
+  int32_t n_merge_items;
+  float scale_log2e;       // scale * log2(e): scores are kept in log2 units
+};
+
+// Launchers (defined next to their kernels).  Each returns a hipError_t.
+hipError_t launch_row_kernel(const AttnParams& p, int head_dim, hipStream_t st);
+hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st);
+hipError_t launch_merge_kernel(const AttnParams& p, int head_dim, hipStream_t st);
+hipError_t launch_pack(const void* pool, void* staging, const int32_t* dev_ids, int32_t n,
+                       size_t block_bytes, hipStream_t st);
+hipError_t launch_unpack(void* pool, const void* staging, const int32_t* dev_ids, int32_t n,
+                         size_t block_bytes, hipStream_t st);
+
+}  // namespace ic

@@ -1,0 +1,78 @@
+// Gather / scatter of whole KV blocks between the paged pool and a contiguous staging buffer:
+// the device half of the swap of Section 3.2 / 4.1, done in one launch for any number of
+// scattered blocks instead of one launch per discontinuous region.
+//
+// Pure byte movement, HBM-bound.  Every lane moves 16 bytes per access and keeps kUnroll
+// independent loads in flight before the first store, so one workgroup has kChunk bytes in
+// flight; the grid is (blocks in the list) x (chunks per block), far more than 256 workgroups.
+#include "ic_internal.h"
+
+namespace ic {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 8;
+constexpr int kChunk = kThreads * 16 * kUnroll;  // 32 KiB per workgroup
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+// PACK: staging[i] <- pool[ids[i]];  !PACK: pool[ids[i]] <- staging[i].
+template <bool PACK>
+__global__ __launch_bounds__(kThreads) void swap_blocks_kernel(char* __restrict__ pool,
+                                                               char* __restrict__ staging,
+                                                               const int32_t* __restrict__ ids,
+                                                               uint32_t block_bytes,
+                                                               uint32_t chunks_per_block) {
+  const uint32_t wg = blockIdx.x;
+  const uint32_t i = wg / chunks_per_block;
+  const uint32_t c = wg - i * chunks_per_block;
+  const int64_t id = ids[i];
+  const char* src;
+  char* dst;
+  if (PACK) {
+    src = pool + id * (int64_t)block_bytes;
+    dst = staging + (int64_t)i * block_bytes;
+  } else {
+    src = staging + (int64_t)i * block_bytes;
+    dst = pool + id * (int64_t)block_bytes;
+  }
+  const uint32_t off0 = c * kChunk + threadIdx.x * 16;
+  u32x4 v[kUnroll];
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t off = off0 + u * (kThreads * 16);
+    if (off < block_bytes) v[u] = __builtin_nontemporal_load((const u32x4*)(src + off));
+  }
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t off = off0 + u * (kThreads * 16);
+    if (off < block_bytes) __builtin_nontemporal_store(v[u], (u32x4*)(dst + off));
+  }
+}
+
+template <bool PACK>
+hipError_t launch_swap(char* pool, char* staging, const int32_t* dev_ids, int32_t n,
+                       size_t block_bytes, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  const uint32_t chunks = (uint32_t)((block_bytes + kChunk - 1) / kChunk);
+  const uint64_t grid = (uint64_t)n * chunks;
+  if (grid > 0x7fffffffull || block_bytes > 0xffffffffull) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(swap_blocks_kernel<PACK>, dim3((uint32_t)grid), dim3(kThreads), 0, st, pool,
+                     staging, dev_ids, (uint32_t)block_bytes, chunks);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_pack(const void* pool, void* staging, const int32_t* dev_ids, int32_t n,
+                       size_t block_bytes, hipStream_t st) {
+  return launch_swap<true>((char*)pool, (char*)staging, dev_ids, n, block_bytes, st);
+}
+
+hipError_t launch_unpack(void* pool, const void* staging, const int32_t* dev_ids, int32_t n,
+                         size_t block_bytes, hipStream_t st) {
+  return launch_swap<false>((char*)pool, (char*)staging, dev_ids, n, block_bytes, st);
+}
+
+}  // namespace ic

@@ -1,0 +1,91 @@
+"""HIP pack / unpack against the memcpy oracle, bit for bit (swap of scattered blocks, Section 3.2)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2402_01869_amd import binding as B
+from paper_2402_01869_amd import workloads as W
+from gpu_common import DEV
+
+pytestmark = pytest.mark.gpu
+
+
+def _roundtrip(cfg, pool_host: np.ndarray, src, dst):
+    """pool_host uint8 [blocks][block_bytes].  Returns nothing; asserts bit-exactness everywhere."""
+    bb = cfg.block_bytes
+    pool_t = torch.from_numpy(pool_host).to(DEV)
+    pool = B.KvPool(B.make_cfg(cfg.pool_blocks, cfg.num_heads, cfg.head_dim), pool_t.data_ptr(), pool_t.numel())
+    assert pool.block_bytes == bb
+    n = len(src)
+    staging = torch.full((n * bb,), 0xA5, dtype=torch.uint8, device=DEV)
+    pool.kv_pack_blocks(src, staging.data_ptr(), staging.numel())
+    torch.cuda.synchronize()
+    want_staging = oracle.pack_blocks(pool_host, src)
+    assert np.array_equal(staging.cpu().numpy().reshape(n, bb), want_staging)
+    assert np.array_equal(pool_t.cpu().numpy(), pool_host), "pack must not write the pool"
+    pool.kv_unpack_blocks(dst, staging.data_ptr(), staging.numel())
+    torch.cuda.synchronize()
+    want_pool = pool_host.copy()
+    oracle.unpack_blocks(want_pool, dst, want_staging)
+    assert np.array_equal(pool_t.cpu().numpy(), want_pool)
+    pool.close()
+
+
+def test_tiny_swap_bit_exact():
+    cfg = W.TINY_SWAP
+    src, dst = W.make_swap_lists(cfg)
+    _roundtrip(cfg, W.random_pool_bytes(cfg), src, dst)
+
+
+@pytest.mark.parametrize("H,D,n", [(1, 64, 1), (3, 64, 5), (5, 128, 7), (2, 256, 3)])
+def test_odd_shapes_and_duplicate_sources(H, D, n):
+    cfg = W.SwapConfig("odd", 7, H, D, 16, 11, n)
+    rng = np.random.default_rng(H * 1000 + D + n)
+    pool_host = rng.integers(0, 256, size=(cfg.pool_blocks, cfg.block_bytes), dtype=np.uint8)
+    src = rng.integers(0, cfg.pool_blocks, size=n).astype(np.int32)   # may repeat
+    dst = rng.permutation(cfg.pool_blocks)[:n].astype(np.int32)
+    _roundtrip(cfg, pool_host, src, dst)
+
+
+def test_full_kv_swap_config_bit_exact():
+    """13B-shaped swap: 2000 of 20000 blocks of 320 KiB, whole pool compared after the round trip."""
+    cfg = W.KV_SWAP
+    src, dst = W.make_swap_lists(cfg)
+    pool_t = torch.empty((cfg.pool_blocks, cfg.block_bytes), dtype=torch.uint8, device=DEV)
+    W.fill_bytes_device(pool_t, cfg.seed)
+    pool_host = pool_t.cpu().numpy()
+    pool = B.KvPool(B.make_cfg(cfg.pool_blocks, cfg.num_heads, cfg.head_dim), pool_t.data_ptr(), pool_t.numel())
+    staging = torch.zeros((cfg.n_move, cfg.block_bytes), dtype=torch.uint8, device=DEV)
+    pool.kv_pack_blocks(src, staging.data_ptr(), staging.numel())
+    pool.kv_unpack_blocks(dst, staging.data_ptr(), staging.numel())
+    torch.cuda.synchronize()
+    want_staging = oracle.pack_blocks(pool_host, src)
+    assert np.array_equal(staging.cpu().numpy(), want_staging)
+    oracle.unpack_blocks(pool_host, dst, want_staging)
+    got = pool_t.cpu().numpy()
+    assert np.array_equal(got, pool_host)
+    # swapped-in context equals the swapped-out one
+    assert np.array_equal(got[dst], got[src])
+    pool.close()
+
+
+def test_errors_leave_memory_untouched():
+    cfg = W.TINY_SWAP
+    pool_host = W.random_pool_bytes(cfg)
+    pool_t = torch.from_numpy(pool_host).to(DEV)
+    pool = B.KvPool(B.make_cfg(cfg.pool_blocks, cfg.num_heads, cfg.head_dim), pool_t.data_ptr(), pool_t.numel())
+    bb = cfg.block_bytes
+    staging = torch.full((4 * bb,), 7, dtype=torch.uint8, device=DEV)
+    sp, sb = staging.data_ptr(), staging.numel()
+    assert pool.kv_pack_blocks([0, 64], sp, sb, check=False) == B.IC_ERANGE
+    assert pool.kv_pack_blocks([-1], sp, sb, check=False) == B.IC_ERANGE
+    assert pool.kv_unpack_blocks([3, 3], sp, sb, check=False) == B.IC_EDUP
+    assert pool.kv_pack_blocks([1, 2, 3, 4, 5], sp, sb, check=False) == B.IC_ESIZE
+    assert pool.kv_pack_blocks([1], sp + 8, sb - 8, check=False) == B.IC_EALIGN
+    assert pool.kv_pack_blocks([1], pool_t.data_ptr() + bb, bb, check=False) == B.IC_EINVAL  # overlaps pool
+    assert pool.kv_pack_blocks([], sp, sb, check=False) == B.IC_OK
+    torch.cuda.synchronize()
+    assert (staging.cpu().numpy() == 7).all()
+    assert np.array_equal(pool_t.cpu().numpy(), pool_host)
+    pool.close()
