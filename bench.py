@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the intercept hot path on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic batch:
+    paged_attn_mixed over the 13B-shaped mixed batch (128 decode sequences + 8 recomputation
+    chunks of 512 rows), then kv_pack_blocks and kv_unpack_blocks of 2000 scattered 320 KiB
+    blocks (the 13B-shaped swap).
+Inputs are resident in HBM before the timed region; the per-call descriptor upload is inside it.
+Prints ONE JSON line.  `python bench.py --gpus N` with N > 1 exits: this path runs on one GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="mixed_13b", choices=["mixed_13b", "gptj_decode", "long_ctx", "tiny"])
+    ap.add_argument("--decode-part", type=int, default=0)
+    ap.add_argument("--span-part", type=int, default=0)
+    ap.add_argument("--span-kernel", type=int, default=0)
+    ap.add_argument("--row-variant", type=int, default=0)
+    ap.add_argument("--no-swap", action="store_true", help="time the attention call only")
+    ap.add_argument("--decode-only", action="store_true", help="drop the recomputation spans from the batch")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target oracle time for the CPU sample")
+    return ap.parse_args()
+
+
+def cpu_baseline(batch, pool_t, q_bits, target_s):
+    """Time the fp64 oracle (as it stands) on a bounded sample of the same batch, on the host cores."""
+    import torch
+    import oracle
+    from paper_2402_01869_amd import workloads as W
+
+    def fetch(ids):
+        idx = torch.from_numpy(np.asarray(ids)).to(pool_t.device)
+        return pool_t.view(torch.int16)[idx].cpu().numpy().view(np.uint16)
+
+    rng = np.random.default_rng(1)
+    dec = [s for s in range(batch.num_seqs) if batch.q_len[s] == 1]
+    spans = [s for s in range(batch.num_seqs) if batch.q_len[s] > 1]
+    # calibrate on two decode sequences, then size the sample to the target time
+    probe = dec[:2] if dec else spans[:1]
+    small, sub = W.compact_referenced(batch, probe, fetch)
+    t0 = time.perf_counter()
+    oracle.paged_attn_items(small, sub.ctx_len, sub.q_len, sub.q_start, sub.block_tables, q_bits, sub.scale,
+                            np.arange(len(probe)), np.zeros(len(probe)))
+    dt = time.perf_counter() - t0
+    keys_probe = int(sum(int(batch.ctx_len[s]) - int(batch.q_len[s]) + 1 for s in probe))
+    keys_per_s = keys_probe / max(dt, 1e-6)
+    budget_keys = keys_per_s * target_s
+    items = []       # (seq, row)
+    used = 0
+    for s in dec:
+        k = int(batch.ctx_len[s])
+        if used + k > budget_keys * 0.5:
+            break
+        items.append((s, 0)); used += k
+    n_dec = len(items)
+    for s in spans:
+        n, c = int(batch.q_len[s]), int(batch.ctx_len[s])
+        for i in rng.permutation(n)[:max(1, n // 64)]:
+            k = c - n + int(i) + 1
+            if used + k > budget_keys:
+                break
+            items.append((s, int(i))); used += k
+    seqs = sorted({s for s, _ in items})
+    remap = {s: j for j, s in enumerate(seqs)}
+    small, sub = W.compact_referenced(batch, seqs, fetch)
+    iseq = np.array([remap[s] for s, _ in items], dtype=np.int32)
+    irow = np.array([i for _, i in items], dtype=np.int32)
+    t0 = time.perf_counter()
+    oracle.paged_attn_items(small, sub.ctx_len, sub.q_len, sub.q_start, sub.block_tables, q_bits, sub.scale, iseq, irow)
+    dt = time.perf_counter() - t0
+    return {"value": used * batch.token_bytes / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": f"{n_dec} decode rows + {len(items) - n_dec} span rows of the same batch "
+                      f"({used} visible keys x {batch.token_bytes} B of KV per key, counted per row)"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this hot path runs on ONE GPU (no sharding or collectives are built); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    from paper_2402_01869_amd import binding as B
+    from paper_2402_01869_amd import workloads as W
+
+    B.lib()  # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    acfg = {"mixed_13b": W.MIXED_13B, "gptj_decode": W.GPTJ_DECODE, "long_ctx": W.LONG_CTX, "tiny": W.TINY}[args.workload]
+    scfg = W.TINY_SWAP if args.workload == "tiny" else W.KV_SWAP
+    if args.decode_only:
+        import dataclasses
+        acfg = dataclasses.replace(acfg, n_span=0)
+    H, D = acfg.num_heads, acfg.head_dim
+
+    # ---- attention inputs: one pool, two batches (different tables) alternated between steps
+    pool_t = torch.empty(W.pool_shape(acfg.pool_blocks, H, 16, D), dtype=torch.bfloat16, device=dev)
+    W.fill_pool_device_normal(pool_t, acfg.seed)
+    pool = B.KvPool.from_tensor(pool_t, H, D)
+    pool.set_tuning(args.decode_part, args.span_part, args.span_kernel, args.row_variant)
+    batches = [W.make_batch(acfg, acfg.seed), W.make_batch(acfg, acfg.seed + 1000)]
+    descs, qs, outs = [], [], []
+    ws_bytes = 0
+    for i, b in enumerate(batches):
+        d = B.HostDesc.from_batch(b, flags=0)
+        q_bits = W.randn_bf16((b.total_q_rows, H, D), np.random.default_rng(acfg.seed + 7 + i))
+        descs.append(d)
+        qs.append((torch.from_numpy(q_bits.view(np.int16)).to(dev), q_bits))
+        outs.append(torch.zeros((b.total_q_rows, H, D), dtype=torch.int16, device=dev))
+        ws_bytes = max(ws_bytes, pool.workspace_bytes(d))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    # ---- swap inputs: its own pool (config shape), two staging buffers alternated
+    do_swap = not args.no_swap
+    if do_swap:
+        spool_t = torch.empty((scfg.pool_blocks, scfg.block_bytes), dtype=torch.uint8, device=dev)
+        W.fill_bytes_device(spool_t, scfg.seed)
+        spool = B.KvPool(B.make_cfg(scfg.pool_blocks, scfg.num_heads, scfg.head_dim), spool_t.data_ptr(), spool_t.numel())
+        src, dst = W.make_swap_lists(scfg)
+        stagings = [torch.empty((scfg.n_move, scfg.block_bytes), dtype=torch.uint8, device=dev) for _ in range(2)]
+        sbytes = stagings[0].numel()
+
+    stream = torch.cuda.current_stream().cuda_stream
+
+    # validated pass (full host checks), then trusted descriptors for the timed loop
+    for i in range(2):
+        pool.paged_attn_mixed(descs[i], qs[i][0].data_ptr(), outs[i].data_ptr(), ws.data_ptr(), ws.numel(), stream)
+        if do_swap:
+            spool.kv_pack_blocks(src, stagings[i].data_ptr(), sbytes, stream)
+    torch.cuda.synchronize()
+    for d in descs:
+        d.struct.flags = B.IC_FLAG_TRUSTED
+
+    def step(i):
+        k = i & 1
+        pool.paged_attn_mixed(descs[k], qs[k][0].data_ptr(), outs[k].data_ptr(), ws.data_ptr(), ws.numel(), stream)
+        if do_swap:
+            spool.kv_pack_blocks(src, stagings[k].data_ptr(), sbytes, stream)
+            spool.kv_unpack_blocks(dst, stagings[k ^ 1].data_ptr(), sbytes, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    pool.prof_begin(8 * args.steps + 8)
+    if do_swap:
+        spool.prof_begin(4 * args.steps + 8)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = pool.prof_end()
+    if do_swap:
+        sp = spool.prof_end()
+        prof["pack"], prof["unpack"] = sp["pack"], sp["unpack"]
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kv_bytes = float(np.mean([b.kv_bytes() for b in batches]))
+    dec_bytes = float(np.mean([int(b.ctx_len[b.q_len == 1].astype(np.int64).sum()) * b.token_bytes for b in batches]))
+    span_flops = float(np.mean([b.span_flops() for b in batches]))
+    swap_moved = 2.0 * scfg.n_move * scfg.block_bytes if do_swap else 0.0   # read + write, per call
+    step_bytes = kv_bytes + 2 * swap_moved
+
+    def avg_ms(k):
+        return prof[k]["total_ms"] / prof[k]["launches"] if prof[k]["launches"] else None
+
+    plan = pool.plan_query(descs[0])
+    attn_ms = sum((avg_ms(k) or 0.0) * (prof[k]["launches"] / args.steps) for k in ("row", "tile", "merge"))
+    kernels = {}
+    for k in ("row", "tile", "merge", "pack", "unpack"):
+        if prof[k]["launches"]:
+            kernels[k] = {"launches": prof[k]["launches"], "avg_ms": round(avg_ms(k), 5)}
+
+    # dominant kernel of the step = the row kernel (HBM-bound).  Its algorithmic bytes per launch:
+    # the KV of every row it is handed, each sequence's context counted once.
+    row_rows_bytes = kv_bytes if plan["tile_items"] == 0 else dec_bytes
+    row_ms = avg_ms("row")
+    roofline = None
+    if row_ms:
+        ach = row_rows_bytes / (row_ms * 1e-3) / 1e9
+        roofline = {"kernel": "row_attn_kernel", "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "bytes_per_launch": row_rows_bytes}
+
+    result = {
+        "metric": "mixed paged-attn KV-read GB/s (% HBM peak); swap pack/unpack GB/s",
+        "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "unit": "GB/s",
+        "value_definition": "algorithmic bytes of one step (KV bytes read once per sequence + pack read+write + "
+                            "unpack read+write) / wall time of the step",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{acfg.name} attention ({acfg.n_decode} decode + {acfg.n_span}x{acfg.span_len}-row spans, "
+                               f"H{H} D{D}, pool {acfg.pool_blocks} blocks)"
+                               + (f" + {scfg.name} ({scfg.n_move} of {scfg.pool_blocks} blocks x {scfg.block_bytes // 1024} KiB)" if do_swap else ""),
+                   "decode_part_tokens": args.decode_part, "span_part_tokens": args.span_part, "span_kernel": args.span_kernel},
+        "attn": {"kv_bytes": kv_bytes, "ms": round(attn_ms, 4),
+                 "kv_read_GBps": round(kv_bytes / (attn_ms * 1e-3) / 1e9, 1) if attn_ms else None,
+                 "frac_hbm_peak": round(kv_bytes / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) if attn_ms else None,
+                 "span_flops": span_flops,
+                 "span_mfma_frac": (round(span_flops / (avg_ms("tile") * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
+                                    if prof["tile"]["launches"] else None),
+                 "plan": plan},
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    if do_swap:
+        for k in ("pack", "unpack"):
+            g = swap_moved / (avg_ms(k) * 1e-3) / 1e9
+            result[k] = {"moved_bytes": swap_moved, "GBps": round(g, 1), "frac_hbm_peak": round(g / HBM_PEAK_GBPS, 4)}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(batches[0], pool_t, qs[0][1], args.cpu_seconds)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -129,7 +129,7 @@ typedef struct {
   int32_t decode_part_tokens; /* keys per work item of a decode row                          */
   int32_t span_part_tokens;   /* keys per work item of a span's query tile                   */
   int32_t span_kernel;        /* 0 = built-in choice, 1 = row-by-row vector kernel, 2 = MFMA tiles */
-  int32_t reserved;
+  int32_t row_variant;        /* vector-kernel build: bit 0 = prefetch two tiles ahead, bit 1 = cached (not non-temporal) KV loads */
 } ic_tuning;
 int ic_pool_set_tuning(ic_pool* pool, const ic_tuning* tuning);
 

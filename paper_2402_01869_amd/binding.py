@@ -48,7 +48,7 @@ class BatchDesc(C.Structure):
 
 
 class Tuning(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("decode_part_tokens", "span_part_tokens", "span_kernel", "reserved")]
+    _fields_ = [(n, C.c_int32) for n in ("decode_part_tokens", "span_part_tokens", "span_kernel", "row_variant")]
 
 
 class PlanInfo(C.Structure):
@@ -180,8 +180,8 @@ class KvPool:
     def block_bytes(self) -> int:
         return int(lib().kv_block_bytes(self._h))
 
-    def set_tuning(self, decode_part_tokens=0, span_part_tokens=0, span_kernel=0):
-        t = Tuning(int(decode_part_tokens), int(span_part_tokens), int(span_kernel), 0)
+    def set_tuning(self, decode_part_tokens=0, span_part_tokens=0, span_kernel=0, row_variant=0):
+        t = Tuning(int(decode_part_tokens), int(span_part_tokens), int(span_kernel), int(row_variant))
         rc = lib().ic_pool_set_tuning(self._h, C.byref(t))
         if rc != IC_OK:
             raise InferceptError(rc, "ic_pool_set_tuning")

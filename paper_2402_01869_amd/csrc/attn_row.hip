@@ -66,16 +66,20 @@ struct Tile {
   u32x4 v[Geo<D>::kLoads];
 };
 
-template <int D>
+template <int D, bool NT>
 __device__ __forceinline__ void load_tile(Tile<D>& t, const char* pool, int64_t blk, int head,
                                           int H, int lane) {
   constexpr int kTileBytes = kBlockSize * D * 2;
   const char* kb = pool + ((blk * 2) * H + head) * (int64_t)kTileBytes + lane * 16;
   const char* vb = kb + (int64_t)H * kTileBytes;
 #pragma unroll
-  for (int j = 0; j < Geo<D>::kLoads; ++j) t.k[j] = *(const u32x4*)(kb + j * 1024);
+  for (int j = 0; j < Geo<D>::kLoads; ++j)
+    t.k[j] = NT ? __builtin_nontemporal_load((const u32x4*)(kb + j * 1024))
+                : *(const u32x4*)(kb + j * 1024);
 #pragma unroll
-  for (int j = 0; j < Geo<D>::kLoads; ++j) t.v[j] = *(const u32x4*)(vb + j * 1024);
+  for (int j = 0; j < Geo<D>::kLoads; ++j)
+    t.v[j] = NT ? __builtin_nontemporal_load((const u32x4*)(vb + j * 1024))
+                : *(const u32x4*)(vb + j * 1024);
 }
 
 // Consume one 16-token tile.  n_valid < 16 only for the last, partial block of a sequence: its
@@ -132,10 +136,9 @@ __device__ __forceinline__ void consume_tile(const Tile<D>& t, const float (&qf)
   }
 }
 
-template <int D>
+template <int D, int PF, bool NT>  // PF = tiles prefetched ahead, NT = non-temporal KV loads
 __global__ __launch_bounds__(kRowWaves * 64) void row_attn_kernel(AttnParams p) {
   using G = Geo<D>;
-  constexpr int PF = 1;           // tiles prefetched ahead
   constexpr int STAGES = PF + 1;  // register buffers
 
   const int H = p.num_heads;
@@ -175,7 +178,7 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_attn_kernel(AttnParams p) 
   Tile<D> buf[STAGES];
 #pragma unroll
   for (int s = 0; s < PF; ++s)
-    if (s < nb_w) load_tile<D>(buf[s], pool, __builtin_amdgcn_readlane(my_id, s), head, H, lane);
+    if (s < nb_w) load_tile<D, NT>(buf[s], pool, __builtin_amdgcn_readlane(my_id, s), head, H, lane);
 
   for (int it0 = 0; it0 < nb_w; it0 += STAGES) {
 #pragma unroll
@@ -183,7 +186,7 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_attn_kernel(AttnParams p) 
       const int i = it0 + s;
       if (i < nb_w) {
         if (i + PF < nb_w)
-          load_tile<D>(buf[(s + PF) % STAGES], pool, __builtin_amdgcn_readlane(my_id, i + PF), head,
+          load_tile<D, NT>(buf[(s + PF) % STAGES], pool, __builtin_amdgcn_readlane(my_id, i + PF), head,
                        H, lane);
         const int tok0 = k_begin + (w + kRowWaves * i) * kBlockSize;
         const int n_valid = k_end - tok0;
@@ -265,12 +268,22 @@ hipError_t launch_row_kernel(const AttnParams& p, int head_dim, hipStream_t st) 
   const uint64_t grid = (uint64_t)p.n_row_items * p.num_heads;
   if (grid > 0x7fffffffull) return hipErrorInvalidValue;
   const dim3 g((uint32_t)grid), b(kRowWaves * 64);
+#define IC_ROW_CASE(DD)                                                                       \
+  case DD:                                                                                    \
+    switch (p.row_variant & 3) {                                                              \
+      case 0: hipLaunchKernelGGL((row_attn_kernel<DD, 1, true>), g, b, 0, st, p); break;       \
+      case 1: hipLaunchKernelGGL((row_attn_kernel<DD, 2, true>), g, b, 0, st, p); break;       \
+      case 2: hipLaunchKernelGGL((row_attn_kernel<DD, 1, false>), g, b, 0, st, p); break;      \
+      default: hipLaunchKernelGGL((row_attn_kernel<DD, 2, false>), g, b, 0, st, p); break;     \
+    }                                                                                         \
+    break;
   switch (head_dim) {
-    case 64: hipLaunchKernelGGL(row_attn_kernel<64>, g, b, 0, st, p); break;
-    case 128: hipLaunchKernelGGL(row_attn_kernel<128>, g, b, 0, st, p); break;
-    case 256: hipLaunchKernelGGL(row_attn_kernel<256>, g, b, 0, st, p); break;
+    IC_ROW_CASE(64)
+    IC_ROW_CASE(128)
+    IC_ROW_CASE(256)
     default: return hipErrorInvalidValue;
   }
+#undef IC_ROW_CASE
   return hipGetLastError();
 }
 

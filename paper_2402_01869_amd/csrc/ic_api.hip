@@ -138,7 +138,7 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   ps.row_part = t.decode_part_tokens > 0 ? round64(t.decode_part_tokens) : kDefaultRowPart;
   ps.row_part = std::min(ps.row_part, kMaxRowPart);
   ps.span_part = t.span_part_tokens > 0 ? round64(t.span_part_tokens) : kDefaultSpanPart;
-  ps.spans_as_rows = (t.span_kernel != 2);  // MFMA tiles only when asked, until they are the default
+  ps.spans_as_rows = (t.span_kernel == 1);  // default: MFMA tiles
   ic_plan_info& in = ps.info;
   for (int s = 0; s < d->num_seqs; ++s) {
     const int c = d->ctx_len[s], n = d->q_len[s];
@@ -182,7 +182,7 @@ void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
   TileItem* tiles = (TileItem*)(img + ps.off_tile);
   MergeItem* merges = (MergeItem*)(img + ps.off_merge);
   int64_t nbt = 0;
-  int nrow = 0, ntile = 0, nmerge = 0, slot = 0;
+  int nrow = 0, ntiles = 0, nmerge = 0, slot = 0;
   for (int s = 0; s < d->num_seqs; ++s) {
     const int c = d->ctx_len[s], n = d->q_len[s];
     const int nb = (c + kBlockSize - 1) / kBlockSize;
@@ -207,29 +207,42 @@ void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
         }
       }
     } else {
-      for (int r0 = 0; r0 < n; r0 += kTileRows) {
+      // slots first (per tile: rows x partitions), then items ordered partition-major so that the
+      // query tiles which read the same keys are dispatched next to each other
+      const int ntile = (n + kTileRows - 1) / kTileRows;
+      int max_parts = 0;
+      std::vector<int> tile_slot0((size_t)ntile, -1), tile_parts((size_t)ntile, 0);
+      for (int ti = 0; ti < ntile; ++ti) {
+        const int r0 = ti * kTileRows;
         const int nr = std::min(kTileRows, n - r0);
-        const int pos0 = c - n + r0;
-        const int klen = pos0 + nr;
+        const int klen = c - n + r0 + nr;
         const int parts = (klen + ps.span_part - 1) / ps.span_part;
-        const int slot0 = parts > 1 ? slot : -1;
+        tile_parts[ti] = parts;
+        max_parts = std::max(max_parts, parts);
         if (parts > 1) {
+          tile_slot0[ti] = slot;
           for (int r = 0; r < nr; ++r)
             merges[nmerge++] = MergeItem{d->q_start[s] + r0 + r, slot + r * parts, parts, 0};
           slot += parts * nr;
         }
-        for (int k = 0; k < parts; ++k) {
-          TileItem& it = tiles[ntile++];
+      }
+      for (int k = 0; k < max_parts; ++k)
+        for (int ti = 0; ti < ntile; ++ti) {
+          if (k >= tile_parts[ti]) continue;
+          const int r0 = ti * kTileRows;
+          const int nr = std::min(kTileRows, n - r0);
+          const int pos0 = c - n + r0;
+          const int klen = pos0 + nr;
+          TileItem& it = tiles[ntiles++];
           it.seq = s;
           it.qrow0 = d->q_start[s] + r0;
           it.n_rows = nr;
           it.pos0 = pos0;
           it.k_begin = k * ps.span_part;
           it.k_end = std::min(klen, (k + 1) * ps.span_part);
-          it.slot0 = parts > 1 ? slot0 + k : -1;
-          it.nparts = parts;
+          it.slot0 = tile_parts[ti] > 1 ? tile_slot0[ti] + k : -1;
+          it.nparts = tile_parts[ti];
         }
-      }
     }
   }
 }
@@ -350,7 +363,7 @@ int ic_check_ids(const ic_pool_cfg* cfg, const int32_t* host_ids, int32_t n, int
 int ic_pool_set_tuning(ic_pool* pool, const ic_tuning* tuning) {
   if (!pool || !tuning) return IC_ENULL;
   if (tuning->decode_part_tokens < 0 || tuning->span_part_tokens < 0 || tuning->span_kernel < 0 ||
-      tuning->span_kernel > 2)
+      tuning->span_kernel > 2 || tuning->row_variant < 0 || tuning->row_variant > 3)
     return IC_EINVAL;
   pool->tune = *tuning;
   return IC_OK;
@@ -411,6 +424,7 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
   p.n_tile_items = ps.info.tile_items;
   p.n_merge_items = ps.info.merge_rows;
   p.scale_log2e = desc->scale * 1.4426950408889634f;
+  p.row_variant = pool->tune.row_variant;
 
   const int D = pool->cfg.head_dim;
   if (p.n_tile_items > 0) {

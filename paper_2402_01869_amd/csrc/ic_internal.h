@@ -59,6 +59,7 @@ struct AttnParams {
   int32_t n_tile_items;
   int32_t n_merge_items;
   float scale_log2e;       // scale * log2(e): scores are kept in log2 units
+  int32_t row_variant;     // row-kernel build: bit0 = prefetch depth 2, bit1 = plain (cached) loads
 };
 
 // Launchers (defined next to their kernels).  Each returns a hipError_t.

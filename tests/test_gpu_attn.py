@@ -36,7 +36,7 @@ def _check_batch(batch, seed, tunings=((0, 0, 0),), tol=TOL):
 
 def test_tiny_config_default_and_forced_split():
     batch = W.make_batch(W.TINY)
-    _check_batch(batch, W.TINY.seed, tunings=((0, 0, 1), (64, 64, 1), (128, 64, 1)))
+    _check_batch(batch, W.TINY.seed, tunings=((0, 0, 0), (64, 64, 0), (0, 0, 1), (64, 64, 1), (128, 64, 1)))
 
 
 @pytest.mark.parametrize("D", [64, 128, 256])
@@ -47,7 +47,17 @@ def test_edge_lengths_rows(D, H):
     qlen = [1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 40, 33]
     rng = np.random.default_rng(100 + D + H)
     batch = W.assemble_batch(H, D, 16, 96, ctx, qlen, rng)
-    _check_batch(batch, 555 + D, tunings=((0, 0, 1), (64, 64, 1)))
+    _check_batch(batch, 555 + D, tunings=((0, 0, 0), (64, 64, 0), (0, 0, 1), (64, 64, 1)))
+
+
+@pytest.mark.parametrize("D,H", [(64, 3), (128, 2), (256, 2)])
+def test_spans_across_tiles_and_partitions(D, H):
+    """Spans longer than one 128-row tile, ragged tails, prefill from 0, prefixes that are not multiples of 64."""
+    ctx = [700, 300, 129, 1000, 64, 515]
+    qlen = [200, 300, 128, 257, 1, 130]
+    rng = np.random.default_rng(7 + D)
+    batch = W.assemble_batch(H, D, 16, 256, ctx, qlen, rng)
+    _check_batch(batch, 77 + D, tunings=((0, 0, 0), (128, 128, 0), (64, 256, 0), (256, 64, 0)))
 
 
 def test_gptj_decode_config_full():
@@ -72,6 +82,40 @@ def test_gptj_decode_config_full():
         want = oracle.paged_attn_items(small, sub.ctx_len, sub.q_len, sub.q_start, sub.block_tables, q_bits,
                                        sub.scale, np.arange(len(seqs)), np.zeros(len(seqs)))
         got = W.bf16_bits_to_f64(out[batch.q_start[seqs]])
+        worst = max(worst, float(np.abs(got - want).max()))
+    assert worst <= TOL, worst
+    pool.close()
+
+
+def test_mixed_13b_config_sampled():
+    """13B-shaped mixed batch at full size, in the launch configuration the benchmark times:
+    every decode row and a deterministic sample of span rows (first, last, tile and block edges)."""
+    cfg = W.MIXED_13B
+    batch = W.make_batch(cfg)
+    pool_t = torch.empty(W.pool_shape(cfg.pool_blocks, cfg.num_heads, 16, cfg.head_dim), dtype=torch.bfloat16, device=DEV)
+    W.fill_pool_device_normal(pool_t, cfg.seed)
+    q_bits = W.randn_bf16((batch.total_q_rows, cfg.num_heads, cfg.head_dim), np.random.default_rng(cfg.seed))
+    pool = B.KvPool.from_tensor(pool_t, cfg.num_heads, cfg.head_dim)
+    r = AttnRunner(pool, batch, q_bits, flags=B.IC_FLAG_TRUSTED)
+    out = r.run()
+    assert np.isfinite(W.bf16_bits_to_f64(out)).all()
+
+    def fetch(ids):
+        return from_dev_bits(pool_t.view(torch.int16)[torch.from_numpy(ids).to(DEV)])
+
+    span_rows = [0, 1, 15, 16, 17, 63, 64, 127, 128, 129, 255, 256, 300, 383, 384, 511]
+    worst = 0.0
+    for s0 in range(0, batch.num_seqs, 8):
+        seqs = list(range(s0, min(batch.num_seqs, s0 + 8)))
+        small, sub = W.compact_referenced(batch, seqs, fetch)
+        iseq, irow = [], []
+        for j, s in enumerate(seqs):
+            rows = [0] if batch.q_len[s] == 1 else span_rows
+            iseq += [j] * len(rows); irow += rows
+        want = oracle.paged_attn_items(small, sub.ctx_len, sub.q_len, sub.q_start, sub.block_tables, q_bits,
+                                       sub.scale, iseq, irow)
+        grow = [int(sub.q_start[j]) + i for j, i in zip(iseq, irow)]
+        got = W.bf16_bits_to_f64(out[grow])
         worst = max(worst, float(np.abs(got - want).max()))
     assert worst <= TOL, worst
     pool.close()
