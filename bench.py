@@ -32,6 +32,7 @@ def parse_args():
     ap.add_argument("--span-part", type=int, default=0)
     ap.add_argument("--span-kernel", type=int, default=0)
     ap.add_argument("--row-variant", type=int, default=0)
+    ap.add_argument("--serial-spans", type=int, default=0)
     ap.add_argument("--no-swap", action="store_true", help="time the attention call only")
     ap.add_argument("--decode-only", action="store_true", help="drop the recomputation spans from the batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -40,7 +41,9 @@ def parse_args():
 
 
 def cpu_baseline(batch, pool_t, q_bits, target_s):
-    """Time the fp64 oracle (as it stands) on a bounded sample of the same batch, on the host cores."""
+    """Time the fp64 oracle (as it stands) on a bounded sample of the same batch, on the host cores.
+
+    The sample is sized from a short calibration run so that it costs about target_s seconds."""
     import torch
     import oracle
     from paper_2402_01869_amd import workloads as W
@@ -49,46 +52,42 @@ def cpu_baseline(batch, pool_t, q_bits, target_s):
         idx = torch.from_numpy(np.asarray(ids)).to(pool_t.device)
         return pool_t.view(torch.int16)[idx].cpu().numpy().view(np.uint16)
 
+    def run(items):
+        seqs = sorted({s for s, _ in items})
+        remap = {s: j for j, s in enumerate(seqs)}
+        small, sub = W.compact_referenced(batch, seqs, fetch)
+        iseq = np.array([remap[s] for s, _ in items], dtype=np.int32)
+        irow = np.array([i for _, i in items], dtype=np.int32)
+        t0 = time.perf_counter()
+        oracle.paged_attn_items(small, sub.ctx_len, sub.q_len, sub.q_start, sub.block_tables, q_bits, sub.scale,
+                                iseq, irow)
+        return time.perf_counter() - t0
+
+    def keys_of(items):
+        return int(sum(int(batch.ctx_len[s]) - int(batch.q_len[s]) + i + 1 for s, i in items))
+
     rng = np.random.default_rng(1)
-    dec = [s for s in range(batch.num_seqs) if batch.q_len[s] == 1]
-    spans = [s for s in range(batch.num_seqs) if batch.q_len[s] > 1]
-    # calibrate on two decode sequences, then size the sample to the target time
-    probe = dec[:2] if dec else spans[:1]
-    small, sub = W.compact_referenced(batch, probe, fetch)
-    t0 = time.perf_counter()
-    oracle.paged_attn_items(small, sub.ctx_len, sub.q_len, sub.q_start, sub.block_tables, q_bits, sub.scale,
-                            np.arange(len(probe)), np.zeros(len(probe)))
-    dt = time.perf_counter() - t0
-    keys_probe = int(sum(int(batch.ctx_len[s]) - int(batch.q_len[s]) + 1 for s in probe))
-    keys_per_s = keys_probe / max(dt, 1e-6)
-    budget_keys = keys_per_s * target_s
-    items = []       # (seq, row)
-    used = 0
-    for s in dec:
-        k = int(batch.ctx_len[s])
-        if used + k > budget_keys * 0.5:
+    # candidate rows in a fixed random order: all decode rows, then random span rows
+    dec = [(s, 0) for s in range(batch.num_seqs) if batch.q_len[s] == 1]
+    span = [(s, int(i)) for s in range(batch.num_seqs) if batch.q_len[s] > 1
+            for i in rng.permutation(int(batch.q_len[s]))[:64]]
+    cand = dec + [span[i] for i in rng.permutation(len(span))]
+    probe = cand[:max(32, oracle.num_threads() * 2)]
+    run(probe[:4])                       # page in the library and the thread pool
+    dt = run(probe)
+    rate = keys_of(probe) / max(dt, 1e-6)
+    items, used = [], 0
+    for it in cand:
+        k = keys_of([it])
+        if items and used + k > rate * target_s:
             break
-        items.append((s, 0)); used += k
-    n_dec = len(items)
-    for s in spans:
-        n, c = int(batch.q_len[s]), int(batch.ctx_len[s])
-        for i in rng.permutation(n)[:max(1, n // 64)]:
-            k = c - n + int(i) + 1
-            if used + k > budget_keys:
-                break
-            items.append((s, int(i))); used += k
-    seqs = sorted({s for s, _ in items})
-    remap = {s: j for j, s in enumerate(seqs)}
-    small, sub = W.compact_referenced(batch, seqs, fetch)
-    iseq = np.array([remap[s] for s, _ in items], dtype=np.int32)
-    irow = np.array([i for _, i in items], dtype=np.int32)
-    t0 = time.perf_counter()
-    oracle.paged_attn_items(small, sub.ctx_len, sub.q_len, sub.q_start, sub.block_tables, q_bits, sub.scale, iseq, irow)
-    dt = time.perf_counter() - t0
-    return {"value": used * batch.token_bytes / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
+        items.append(it); used += k
+    dt = run(items)
+    n_dec = sum(1 for s, _ in items if batch.q_len[s] == 1)
+    return {"value": round(used * batch.token_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
             "kind": "oracle", "seconds": round(dt, 3),
             "sample": f"{n_dec} decode rows + {len(items) - n_dec} span rows of the same batch "
-                      f"({used} visible keys x {batch.token_bytes} B of KV per key, counted per row)"}
+                      f"({used} visible keys x {batch.token_bytes} B of KV per key, counted once per row)"}
 
 
 def main():
@@ -117,7 +116,7 @@ def main():
     pool_t = torch.empty(W.pool_shape(acfg.pool_blocks, H, 16, D), dtype=torch.bfloat16, device=dev)
     W.fill_pool_device_normal(pool_t, acfg.seed)
     pool = B.KvPool.from_tensor(pool_t, H, D)
-    pool.set_tuning(args.decode_part, args.span_part, args.span_kernel, args.row_variant)
+    pool.set_tuning(args.decode_part, args.span_part, args.span_kernel, args.row_variant, args.serial_spans)
     batches = [W.make_batch(acfg, acfg.seed), W.make_batch(acfg, acfg.seed + 1000)]
     descs, qs, outs = [], [], []
     ws_bytes = 0
@@ -177,6 +176,15 @@ def main():
         prof["pack"], prof["unpack"] = sp["pack"], sp["unpack"]
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # wall time of the attention call alone (same inputs, separate loop; kernels may overlap inside it)
+    torch.cuda.synchronize()
+    ta = time.perf_counter()
+    for i in range(args.steps):
+        k = i & 1
+        pool.paged_attn_mixed(descs[k], qs[k][0].data_ptr(), outs[k].data_ptr(), ws.data_ptr(), ws.numel(), stream)
+    torch.cuda.synchronize()
+    attn_wall_ms = (time.perf_counter() - ta) * 1e3 / args.steps
     kv_bytes = float(np.mean([b.kv_bytes() for b in batches]))
     dec_bytes = float(np.mean([int(b.ctx_len[b.q_len == 1].astype(np.int64).sum()) * b.token_bytes for b in batches]))
     span_flops = float(np.mean([b.span_flops() for b in batches]))
@@ -187,22 +195,26 @@ def main():
         return prof[k]["total_ms"] / prof[k]["launches"] if prof[k]["launches"] else None
 
     plan = pool.plan_query(descs[0])
-    attn_ms = sum((avg_ms(k) or 0.0) * (prof[k]["launches"] / args.steps) for k in ("row", "tile", "merge"))
+    attn_ms = sum((avg_ms(k) or 0.0) * (prof[k]["launches"] / args.steps) for k in ("row", "tile", "merge", "fused"))
     kernels = {}
-    for k in ("row", "tile", "merge", "pack", "unpack"):
+    for k in ("row", "tile", "merge", "fused", "pack", "unpack"):
         if prof[k]["launches"]:
             kernels[k] = {"launches": prof[k]["launches"], "avg_ms": round(avg_ms(k), 5)}
 
-    # dominant kernel of the step = the row kernel (HBM-bound).  Its algorithmic bytes per launch:
-    # the KV of every row it is handed, each sequence's context counted once.
-    row_rows_bytes = kv_bytes if plan["tile_items"] == 0 else dec_bytes
-    row_ms = avg_ms("row")
+    # Dominant kernel of the step: the fused mixed kernel when the batch has spans and decode rows
+    # (it moves every KV byte of the call once), else the row kernel (decode rows only).
+    # Algorithmic bytes per launch = KV bytes of the rows it is handed, each context counted once.
     roofline = None
-    if row_ms:
-        ach = row_rows_bytes / (row_ms * 1e-3) / 1e9
-        roofline = {"kernel": "row_attn_kernel", "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+    if prof["fused"]["launches"]:
+        dom, dom_name, dom_bytes = "fused", "fused_persist_kernel", kv_bytes
+    else:
+        dom, dom_name = "row", "row_attn_kernel"
+        dom_bytes = kv_bytes if plan["tile_items"] == 0 else dec_bytes
+    if prof[dom]["launches"]:
+        ach = dom_bytes / (avg_ms(dom) * 1e-3) / 1e9
+        roofline = {"kernel": dom_name, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
-                    "bytes_per_launch": row_rows_bytes}
+                    "bytes_per_launch": dom_bytes, "avg_launch_ms": round(avg_ms(dom), 5)}
 
     result = {
         "metric": "mixed paged-attn KV-read GB/s (% HBM peak); swap pack/unpack GB/s",
@@ -217,9 +229,9 @@ def main():
                                f"H{H} D{D}, pool {acfg.pool_blocks} blocks)"
                                + (f" + {scfg.name} ({scfg.n_move} of {scfg.pool_blocks} blocks x {scfg.block_bytes // 1024} KiB)" if do_swap else ""),
                    "decode_part_tokens": args.decode_part, "span_part_tokens": args.span_part, "span_kernel": args.span_kernel},
-        "attn": {"kv_bytes": kv_bytes, "ms": round(attn_ms, 4),
-                 "kv_read_GBps": round(kv_bytes / (attn_ms * 1e-3) / 1e9, 1) if attn_ms else None,
-                 "frac_hbm_peak": round(kv_bytes / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) if attn_ms else None,
+        "attn": {"kv_bytes": kv_bytes, "ms": round(attn_wall_ms, 4), "sum_kernel_ms": round(attn_ms, 4),
+                 "kv_read_GBps": round(kv_bytes / (attn_wall_ms * 1e-3) / 1e9, 1),
+                 "frac_hbm_peak": round(kv_bytes / (attn_wall_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                  "span_flops": span_flops,
                  "span_mfma_frac": (round(span_flops / (avg_ms("tile") * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
                                     if prof["tile"]["launches"] else None),

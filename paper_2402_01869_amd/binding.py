@@ -19,8 +19,8 @@ IC_OK = 0
 IC_ENULL, IC_EINVAL, IC_ERANGE, IC_ESIZE, IC_EALIGN = -1, -2, -3, -4, -5
 IC_EDUP, IC_EUNSUPPORTED, IC_EOVERLAP, IC_EHIP, IC_ENOMEM = -6, -7, -8, -9, -10
 IC_FLAG_TRUSTED = 1
-IC_K_ROW, IC_K_TILE, IC_K_MERGE, IC_K_PACK, IC_K_UNPACK, IC_K_COUNT = 0, 1, 2, 3, 4, 5
-KERNEL_NAMES = ("row", "tile", "merge", "pack", "unpack")
+IC_K_ROW, IC_K_TILE, IC_K_MERGE, IC_K_PACK, IC_K_UNPACK, IC_K_FUSED, IC_K_COUNT = 0, 1, 2, 3, 4, 5, 6
+KERNEL_NAMES = ("row", "tile", "merge", "pack", "unpack", "fused")
 
 EXPORTS = (
     "ic_strerror", "kv_pool_init", "kv_pool_destroy", "kv_block_bytes",
@@ -48,7 +48,8 @@ class BatchDesc(C.Structure):
 
 
 class Tuning(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("decode_part_tokens", "span_part_tokens", "span_kernel", "row_variant")]
+    _fields_ = [(n, C.c_int32) for n in ("decode_part_tokens", "span_part_tokens", "span_kernel", "row_variant",
+                                         "serial_spans")] + [("reserved", C.c_int32 * 3)]
 
 
 class PlanInfo(C.Structure):
@@ -180,8 +181,9 @@ class KvPool:
     def block_bytes(self) -> int:
         return int(lib().kv_block_bytes(self._h))
 
-    def set_tuning(self, decode_part_tokens=0, span_part_tokens=0, span_kernel=0, row_variant=0):
-        t = Tuning(int(decode_part_tokens), int(span_part_tokens), int(span_kernel), int(row_variant))
+    def set_tuning(self, decode_part_tokens=0, span_part_tokens=0, span_kernel=0, row_variant=0, serial_spans=0):
+        t = Tuning(int(decode_part_tokens), int(span_part_tokens), int(span_kernel), int(row_variant),
+                   int(serial_spans), (C.c_int32 * 3)(0, 0, 0))
         rc = lib().ic_pool_set_tuning(self._h, C.byref(t))
         if rc != IC_OK:
             raise InferceptError(rc, "ic_pool_set_tuning")

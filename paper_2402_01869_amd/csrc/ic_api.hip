@@ -14,9 +14,8 @@ using namespace ic;
 namespace {
 
 constexpr int kStagingSlots = 4;       // pinned host buffers cycled by successive calls
-constexpr int kDefaultRowPart = 256;   // keys per decode work item
+constexpr int kDefaultRowPart = 1024;  // keys per decode work item (512 for head_dim 256)
 constexpr int kDefaultSpanPart = 4096; // keys per span-tile work item
-constexpr int kTileRows = 128;         // query rows per MFMA tile work item
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -47,6 +46,7 @@ struct ic_pool {
   int next_slot;
   int32_t* dev_ids;
   size_t dev_ids_cap;
+  int num_cus;           // compute units of the pool's device (0 until the first attention call)
   ProfState prof;
 };
 
@@ -119,14 +119,14 @@ int check_ids(const ic_pool_cfg& cfg, const int32_t* ids, int32_t n, bool distin
 // ---------------------------------------------------------------------------------------
 // Launch plan.  Sizes only (plan_sizes) or the filled descriptor image (plan_fill).
 // Device image layout (all sections 256-byte aligned, in this order):
-//   bt_off[num_seqs] | bt_flat[table_entries] | row_items | tile_items | merge_items
+//   counters[16] | bt_off[num_seqs] | bt_flat[table_entries] | row_items | tile_items | merge_items
 // followed in the workspace by part_o[slots][H][D] and part_ml[slots][H][2].
 // ---------------------------------------------------------------------------------------
 struct PlanSizes {
   ic_plan_info info;
-  int row_part, span_part;
+  int row_part, span_part, tile_rows;
   bool spans_as_rows;
-  size_t off_bt_off, off_bt_flat, off_row, off_tile, off_merge, image_bytes;
+  size_t off_ctr, off_bt_off, off_bt_flat, off_row, off_tile, off_merge, image_bytes;
   size_t off_part_o, off_part_ml, total_bytes;
 };
 
@@ -134,8 +134,11 @@ int round64(int x) { return (x + 63) / 64 * 64; }
 
 void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   std::memset(&ps, 0, sizeof ps);
+  const int kTileRows = tile_rows(pool->cfg.head_dim);
+  ps.tile_rows = kTileRows;
   const ic_tuning& t = pool->tune;
-  ps.row_part = t.decode_part_tokens > 0 ? round64(t.decode_part_tokens) : kDefaultRowPart;
+  ps.row_part = t.decode_part_tokens > 0 ? round64(t.decode_part_tokens)
+                                         : (pool->cfg.head_dim >= 256 ? kDefaultRowPart / 2 : kDefaultRowPart);
   ps.row_part = std::min(ps.row_part, kMaxRowPart);
   ps.span_part = t.span_part_tokens > 0 ? round64(t.span_part_tokens) : kDefaultSpanPart;
   ps.spans_as_rows = (t.span_kernel == 1);  // default: MFMA tiles
@@ -164,6 +167,7 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   }
   const int H = pool->cfg.num_heads, D = pool->cfg.head_dim;
   size_t o = 0;
+  ps.off_ctr = o;     o = align_up(o + sizeof(int32_t) * 16, 256);
   ps.off_bt_off = o;  o = align_up(o + sizeof(int32_t) * (size_t)d->num_seqs, 256);
   ps.off_bt_flat = o; o = align_up(o + sizeof(int32_t) * (size_t)in.table_entries, 256);
   ps.off_row = o;     o = align_up(o + sizeof(RowItem) * (size_t)in.row_items, 256);
@@ -176,6 +180,8 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
 }
 
 void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
+  const int kTileRows = ps.tile_rows;
+  std::memset(img + ps.off_ctr, 0, sizeof(int32_t) * 16);  // work-queue counters start at zero
   int32_t* bt_off = (int32_t*)(img + ps.off_bt_off);
   int32_t* bt_flat = (int32_t*)(img + ps.off_bt_flat);
   RowItem* rows = (RowItem*)(img + ps.off_row);
@@ -328,6 +334,7 @@ int kv_pool_init(const ic_pool_cfg* cfg, void* dev_pool_base, size_t pool_bytes,
   p->next_slot = 0;
   p->dev_ids = nullptr;
   p->dev_ids_cap = 0;
+  p->num_cus = 0;
   *out = p;
   return IC_OK;
 }
@@ -363,7 +370,9 @@ int ic_check_ids(const ic_pool_cfg* cfg, const int32_t* host_ids, int32_t n, int
 int ic_pool_set_tuning(ic_pool* pool, const ic_tuning* tuning) {
   if (!pool || !tuning) return IC_ENULL;
   if (tuning->decode_part_tokens < 0 || tuning->span_part_tokens < 0 || tuning->span_kernel < 0 ||
-      tuning->span_kernel > 2 || tuning->row_variant < 0 || tuning->row_variant > 3)
+      tuning->span_kernel > 2 || tuning->row_variant < 0 || tuning->row_variant > 3 ||
+      tuning->serial_spans < 0 || tuning->serial_spans > 1 || tuning->reserved[0] || tuning->reserved[1] ||
+      tuning->reserved[2])
     return IC_EINVAL;
   pool->tune = *tuning;
   return IC_OK;
@@ -408,6 +417,14 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
   if (hipEventRecord(slot->ev, st) != hipSuccess) return IC_EHIP;
   slot->pending = true;
 
+  const int D = pool->cfg.head_dim;
+  if (pool->num_cus == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
+      return IC_EHIP;
+    pool->num_cus = cus;
+  }
   AttnParams p;
   p.pool = (const uint16_t*)pool->base;
   p.q = (const uint16_t*)dev_q;
@@ -425,15 +442,25 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
   p.n_merge_items = ps.info.merge_rows;
   p.scale_log2e = desc->scale * 1.4426950408889634f;
   p.row_variant = pool->tune.row_variant;
+  p.persist_slots = pool->num_cus * 2;
+  p.counters = (int32_t*)(ws + ps.off_ctr);
 
-  const int D = pool->cfg.head_dim;
-  if (p.n_tile_items > 0) {
-    ProfScope ps_(pool, IC_K_TILE, st);
-    if (launch_tile_kernel(p, D, st) != hipSuccess) return IC_EHIP;
-  }
-  if (p.n_row_items > 0) {
-    ProfScope ps_(pool, IC_K_ROW, st);
-    if (launch_row_kernel(p, D, st) != hipSuccess) return IC_EHIP;
+  // Decode rows are HBM-bound and span tiles are MFMA-bound (the complementarity Section 4.2
+  // builds on): a batch that has both runs them in one fused launch that co-schedules the two
+  // roles on every CU.  serial_spans = 1 keeps the two single-role kernels, one after the other.
+  const bool fused = p.n_tile_items > 0 && p.n_row_items > 0 && !pool->tune.serial_spans && D <= 128;
+  if (fused) {
+    ProfScope ps_(pool, IC_K_FUSED, st);
+    if (launch_fused_kernel(p, D, st) != hipSuccess) return IC_EHIP;
+  } else {
+    if (p.n_tile_items > 0) {
+      ProfScope ps_(pool, IC_K_TILE, st);
+      if (launch_tile_kernel(p, D, st) != hipSuccess) return IC_EHIP;
+    }
+    if (p.n_row_items > 0) {
+      ProfScope ps_(pool, IC_K_ROW, st);
+      if (launch_row_kernel(p, D, st) != hipSuccess) return IC_EHIP;
+    }
   }
   if (p.n_merge_items > 0) {
     ProfScope ps_(pool, IC_K_MERGE, st);

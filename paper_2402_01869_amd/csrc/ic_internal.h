@@ -11,6 +11,9 @@ constexpr int kBlockSize = 16;  // tokens per cache block (the only size built)
 constexpr int kRowWaves = 4;    // waves per workgroup of the row kernel
 constexpr int kMaxRowPart = 4096;  // keys per row-kernel work item: 64 block ids per wave
 
+// Query rows per work item of the MFMA tile kernel (planner and kernel must agree).
+constexpr int tile_rows(int head_dim) { return head_dim > 0 ? 128 : 128; }
+
 // One work item of the row kernel: one query row against keys [k_begin, k_end) of its sequence,
 // for every head (the head is a grid dimension).  32 bytes so a wave reads it with scalar loads.
 struct RowItem {
@@ -22,7 +25,7 @@ struct RowItem {
   int32_t pad[3];
 };
 
-// One work item of the MFMA tile kernel: up to 128 consecutive rows of one span against keys
+// One work item of the MFMA tile kernel: up to tile_rows(D) consecutive rows of one span against keys
 // [k_begin, k_end) (k_end is a bound for the LAST row; earlier rows see fewer keys).
 struct TileItem {
   int32_t seq;
@@ -60,12 +63,15 @@ struct AttnParams {
   int32_t n_merge_items;
   float scale_log2e;       // scale * log2(e): scores are kept in log2 units
   int32_t row_variant;     // row-kernel build: bit0 = prefetch depth 2, bit1 = plain (cached) loads
+  int32_t persist_slots;   // fused kernel: resident workgroups (2 per CU)
+  int32_t* counters;       // 16 work-queue counters, zero when the kernel starts
 };
 
 // Launchers (defined next to their kernels).  Each returns a hipError_t.
 hipError_t launch_row_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_merge_kernel(const AttnParams& p, int head_dim, hipStream_t st);
+hipError_t launch_fused_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_pack(const void* pool, void* staging, const int32_t* dev_ids, int32_t n,
                        size_t block_bytes, hipStream_t st);
 hipError_t launch_unpack(void* pool, const void* staging, const int32_t* dev_ids, int32_t n,

@@ -121,6 +121,49 @@ def test_mixed_13b_config_sampled():
     pool.close()
 
 
+@pytest.mark.timeout(900)
+def test_long_context_config_sampled():
+    """Long-context stress at full size (128 GiB pool, 16 spans of 2048 rows on 16384-token prefixes,
+    split-KV path): every 4th decode sequence and a deterministic sample of span rows."""
+    cfg = W.LONG_CTX
+    free, total = torch.cuda.mem_get_info()
+    need = cfg.pool_blocks * cfg.block_bytes + (8 << 30)
+    if free < need:
+        pytest.skip(f"needs {need >> 30} GiB of free HBM, {free >> 30} available")
+    batch = W.make_batch(cfg)
+    pool_t = torch.empty(W.pool_shape(cfg.pool_blocks, cfg.num_heads, 16, cfg.head_dim), dtype=torch.bfloat16, device=DEV)
+    W.fill_pool_device_normal(pool_t, cfg.seed, chunk_blocks=4096)
+    q_bits = W.randn_bf16((batch.total_q_rows, cfg.num_heads, cfg.head_dim), np.random.default_rng(cfg.seed))
+    pool = B.KvPool.from_tensor(pool_t, cfg.num_heads, cfg.head_dim)
+    r = AttnRunner(pool, batch, q_bits, flags=B.IC_FLAG_TRUSTED)
+    info = pool.plan_query(r.desc)
+    assert info["partial_slots"] > 0 and info["tile_items"] > 16 * 16   # split-KV really in use
+    out = r.run()
+    assert np.isfinite(W.bf16_bits_to_f64(out)).all()
+
+    def fetch(ids):
+        return from_dev_bits(pool_t.view(torch.int16)[torch.from_numpy(ids).to(DEV)])
+
+    span_rows = [0, 1, 15, 16, 17, 127, 128, 1023, 1024, 2047]
+    seq_list = list(range(0, cfg.n_decode, 4)) + list(range(cfg.n_decode, batch.num_seqs))
+    worst = 0.0
+    for s0 in range(0, len(seq_list), 8):
+        seqs = seq_list[s0:s0 + 8]
+        small, sub = W.compact_referenced(batch, seqs, fetch)
+        iseq, irow = [], []
+        for j, s in enumerate(seqs):
+            rows = [0] if batch.q_len[s] == 1 else span_rows
+            iseq += [j] * len(rows); irow += rows
+        want = oracle.paged_attn_items(small, sub.ctx_len, sub.q_len, sub.q_start, sub.block_tables, q_bits,
+                                       sub.scale, iseq, irow)
+        grow = [int(sub.q_start[j]) + i for j, i in zip(iseq, irow)]
+        got = W.bf16_bits_to_f64(out[grow])
+        worst = max(worst, float(np.abs(got - want).max()))
+        del small
+    assert worst <= TOL, worst
+    pool.close()
+
+
 def test_descriptor_errors_launch_nothing():
     batch = W.make_batch(W.TINY)
     pool_bits, q_bits = W.make_host_inputs(batch, 3)

@@ -1,0 +1,151 @@
+"""CPU-only checks of the C-ABI library: exported symbols, validation and launch planning.
+No compute entry point is called here (no GPU in this tier)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2402_01869_amd import binding as B
+from paper_2402_01869_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "infercept_hot.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"kv_pool_init", "paged_attn_mixed", "kv_pack_blocks", "kv_unpack_blocks"} <= set(names)
+    raw = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), f"{n} declared in the header but not exported"
+    assert set(names) == set(B.EXPORTS), "binding.EXPORTS out of sync with the header"
+
+
+def test_strerror_covers_codes():
+    seen = {B.strerror(c) for c in range(0, -11, -1)}
+    assert len(seen) == 11 and "unknown error code" not in seen
+    assert B.strerror(-99) == "unknown error code"
+
+
+def _pool(cfg=None, ptr=0x10000, nbytes=None):
+    cfg = cfg or B.make_cfg(64, 4, 64)
+    bb = cfg.block_size * 2 * cfg.num_kv_heads * cfg.head_dim * 2
+    return B.KvPool(cfg, ptr, cfg.num_blocks * bb if nbytes is None else nbytes)
+
+
+def test_pool_init_validation():
+    # kv_pool_init touches no GPU state, so a made-up (aligned) address is enough on the CPU
+    p = _pool()
+    assert p.block_bytes == 16 * 2 * 4 * 64 * 2
+    p.close()
+    for kw, code in [(dict(cfg=B.make_cfg(64, 4, 96)), B.IC_EUNSUPPORTED),
+                     (dict(cfg=B.make_cfg(64, 4, 64, block_size=32)), B.IC_EUNSUPPORTED),
+                     (dict(cfg=B.make_cfg(64, 8, 64, num_kv_heads=2)), B.IC_EUNSUPPORTED),
+                     (dict(cfg=B.make_cfg(64, 4, 64, dtype=1)), B.IC_EUNSUPPORTED),
+                     (dict(cfg=B.make_cfg(0, 4, 64)), B.IC_EINVAL),
+                     (dict(ptr=0x10008), B.IC_EALIGN),
+                     (dict(ptr=0), B.IC_ENULL),
+                     (dict(nbytes=63 * 16384), B.IC_ESIZE)]:
+        with pytest.raises(B.InferceptError) as e:
+            _pool(**kw)
+        assert e.value.code == code, kw
+
+
+def test_check_batch_codes():
+    cfg = B.make_cfg(64, 4, 64)
+    b = W.make_batch(W.TINY)
+    ok = B.HostDesc.from_batch(b)
+    assert B.check_batch(cfg, ok) == B.IC_OK
+
+    def desc(**kw):
+        a = dict(ctx_len=b.ctx_len.copy(), q_len=b.q_len.copy(), q_start=b.q_start.copy(),
+                 block_tables=b.block_tables.copy(), scale=b.scale, total_q_rows=b.total_q_rows)
+        a.update(kw)
+        return B.HostDesc(**a)
+
+    bt = b.block_tables.copy(); bt[2, 1] = 64
+    assert B.check_batch(cfg, desc(block_tables=bt)) == B.IC_ERANGE
+    bt = b.block_tables.copy(); bt[0, 0] = -1
+    assert B.check_batch(cfg, desc(block_tables=bt)) == B.IC_ERANGE
+    # entries past ceil(ctx/16) are ignored, whatever they hold
+    bt = b.block_tables.copy(); bt[0, -1] = 10 ** 6 if b.ctx_len[0] <= 16 * (bt.shape[1] - 1) else bt[0, -1]
+    assert B.check_batch(cfg, desc(block_tables=bt)) == B.IC_OK
+    c = b.ctx_len.copy(); c[1] = 0
+    assert B.check_batch(cfg, desc(ctx_len=c)) == B.IC_EINVAL
+    q = b.q_len.copy(); q[0] = 0
+    assert B.check_batch(cfg, desc(q_len=q)) == B.IC_EINVAL
+    q = b.q_len.copy(); q[1] = b.ctx_len[1] + 1
+    assert B.check_batch(cfg, desc(q_len=q, total_q_rows=10 ** 4)) == B.IC_EINVAL
+    qs = b.q_start.copy(); qs[3] = qs[2] + 1
+    assert B.check_batch(cfg, desc(q_start=qs)) == B.IC_EOVERLAP
+    qs = b.q_start.copy(); qs[3] = b.total_q_rows - 1
+    assert B.check_batch(cfg, desc(q_start=qs)) == B.IC_EOVERLAP
+    assert B.check_batch(cfg, desc(block_tables=b.block_tables[:, :2])) == B.IC_ESIZE
+    assert B.check_batch(cfg, desc(scale=float("nan"))) == B.IC_EINVAL
+    assert B.check_batch(cfg, desc(scale=-1.0)) == B.IC_EINVAL
+    # rows may leave gaps in the packed array
+    assert B.check_batch(cfg, desc(total_q_rows=b.total_q_rows + 5)) == B.IC_OK
+
+
+def test_check_ids_codes():
+    cfg = B.make_cfg(100, 4, 64)
+    assert B.check_ids(cfg, [1, 5, 5], False) == B.IC_OK
+    assert B.check_ids(cfg, [1, 5, 5], True) == B.IC_EDUP
+    assert B.check_ids(cfg, [0, 99], True) == B.IC_OK
+    assert B.check_ids(cfg, [100], False) == B.IC_ERANGE
+    assert B.check_ids(cfg, [-1], False) == B.IC_ERANGE
+    assert B.check_ids(cfg, [], True) == B.IC_OK
+
+
+def test_plan_counts_and_workspace():
+    p = _pool()
+    b = W.make_batch(W.TINY)
+    d = B.HostDesc.from_batch(b)
+    base = p.plan_query(d)
+    assert base["decode_rows"] == 2 and base["span_rows"] == int(b.q_len[2:].sum())
+    assert base["row_items"] == 2 and base["partial_slots"] == 0 and base["merge_rows"] == 0
+    assert base["tile_items"] == 2            # one 128-row tile per 32-row span, contexts <= 128 keys
+    assert base["table_entries"] == int(sum(-(-int(c) // 16) for c in b.ctx_len))
+    w0 = p.workspace_bytes(d)
+    assert w0 > 0 and w0 % 256 == 0
+    # forcing 64-key partitions splits every context longer than 64 keys
+    p.set_tuning(64, 64, 0)
+    split = p.plan_query(d)
+    want_row_items = sum(-(-int(c) // 64) for c in b.ctx_len[:2])
+    assert split["row_items"] == want_row_items
+    assert split["partial_slots"] > 0 and split["merge_rows"] > 0
+    assert p.workspace_bytes(d) > w0
+    # spans row by row: one work item per (row, partition)
+    p.set_tuning(0, 0, 1)
+    rows = p.plan_query(d)
+    assert rows["tile_items"] == 0 and rows["row_items"] == b.total_q_rows
+    with pytest.raises(B.InferceptError):
+        p.set_tuning(-1, 0, 0)
+    with pytest.raises(B.InferceptError):
+        p.set_tuning(0, 0, 3)
+    bad = B.HostDesc(b.ctx_len, b.q_len + 1000, b.q_start, b.block_tables, b.scale)
+    assert p.workspace_bytes(bad) == 0
+    p.close()
+
+
+def test_full_size_plans_are_sane():
+    """Plans of the benchmark configurations: every key of every row is covered exactly once."""
+    for cfg in (W.GPTJ_DECODE, W.MIXED_13B, W.LONG_CTX):
+        b = W.make_batch(cfg)
+        p = _pool(B.make_cfg(cfg.pool_blocks, cfg.num_heads, cfg.head_dim))
+        d = B.HostDesc.from_batch(b, flags=B.IC_FLAG_TRUSTED)
+        info = p.plan_query(d)
+        assert info["decode_rows"] == cfg.n_decode and info["span_rows"] == cfg.n_span * cfg.span_len
+        assert info["table_entries"] == int(sum(-(-int(c) // 16) for c in b.ctx_len))
+        part = 512 if cfg.head_dim == 256 else 1024
+        assert info["row_items"] == int(sum(-(-int(c) // part) for c in b.ctx_len[:cfg.n_decode]))
+        assert info["tile_items"] >= cfg.n_span * (cfg.span_len // 128)
+        assert 0 < p.workspace_bytes(d) < (4 << 30)
+        p.close()
