@@ -19,6 +19,10 @@ import time
 import numpy as np
 
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
+# command, scaled by the pack kernel's known 640 000 KiB (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 on this GPU);
+# figures and commands in profiles/fused_persist_kernel_mixed_13b.md.  Only valid for the default workload.
+MEASURED_TRAFFIC_BYTES = {"mixed_13b/fused": (3105728 * 2.0 + 75071) * 1024}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
 
@@ -70,7 +74,7 @@ def cpu_baseline(batch, pool_t, q_bits, target_s):
     # candidate rows in a fixed random order: all decode rows, then random span rows
     dec = [(s, 0) for s in range(batch.num_seqs) if batch.q_len[s] == 1]
     span = [(s, int(i)) for s in range(batch.num_seqs) if batch.q_len[s] > 1
-            for i in rng.permutation(int(batch.q_len[s]))[:64]]
+            for i in rng.permutation(int(batch.q_len[s]))]
     cand = dec + [span[i] for i in rng.permutation(len(span))]
     probe = cand[:max(32, oracle.num_threads() * 2)]
     run(probe[:4])                       # page in the library and the thread pool
@@ -213,7 +217,9 @@ def main():
     if prof[dom]["launches"]:
         ach = dom_bytes / (avg_ms(dom) * 1e-3) / 1e9
         roofline = {"kernel": dom_name, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
-                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
+                    "traffic": (MEASURED_TRAFFIC_BYTES.get(f"{args.workload}/{dom}")
+                                if not (args.decode_only or args.decode_part or args.span_part) else None),
                     "bytes_per_launch": dom_bytes, "avg_launch_ms": round(avg_ms(dom), 5)}
 
     result = {
