@@ -203,7 +203,8 @@ def main():
     kernels = {}
     for k in ("row", "tile", "merge", "fused", "pack", "unpack"):
         if prof[k]["launches"]:
-            kernels[k] = {"launches": prof[k]["launches"], "avg_ms": round(avg_ms(k), 5)}
+            kernels[k] = {"launches": prof[k]["launches"], "avg_ms": round(avg_ms(k), 5),
+                          "min_ms": round(prof[k]["min_ms"], 5), "max_ms": round(prof[k]["max_ms"], 5)}
 
     # Dominant kernel of the step: the fused mixed kernel when the batch has spans and decode rows
     # (it moves every KV byte of the call once), else the row kernel (decode rows only).

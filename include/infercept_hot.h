@@ -175,6 +175,8 @@ enum { IC_K_ROW = 0, IC_K_TILE = 1, IC_K_MERGE = 2, IC_K_PACK = 3, IC_K_UNPACK =
 typedef struct {
   int32_t launches[IC_K_COUNT];
   float total_ms[IC_K_COUNT];
+  float min_ms[IC_K_COUNT];
+  float max_ms[IC_K_COUNT];
 } ic_prof_stats;
 int ic_prof_begin(ic_pool* pool, int32_t max_launches);
 int ic_prof_end(ic_pool* pool, ic_prof_stats* out);

@@ -13,7 +13,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libinfercept_hot.so")
+LIB_PATH = os.environ.get("INFERCEPT_HOT_LIB") or os.path.join(_HERE, "libinfercept_hot.so")
 
 IC_OK = 0
 IC_ENULL, IC_EINVAL, IC_ERANGE, IC_ESIZE, IC_EALIGN = -1, -2, -3, -4, -5
@@ -59,7 +59,8 @@ class PlanInfo(C.Structure):
 
 
 class ProfStats(C.Structure):
-    _fields_ = [("launches", C.c_int32 * IC_K_COUNT), ("total_ms", C.c_float * IC_K_COUNT)]
+    _fields_ = [("launches", C.c_int32 * IC_K_COUNT), ("total_ms", C.c_float * IC_K_COUNT),
+                ("min_ms", C.c_float * IC_K_COUNT), ("max_ms", C.c_float * IC_K_COUNT)]
 
 
 class InferceptError(RuntimeError):
@@ -232,5 +233,6 @@ class KvPool:
         rc = lib().ic_prof_end(self._h, C.byref(st))
         if rc != IC_OK:
             raise InferceptError(rc, "ic_prof_end")
-        return {KERNEL_NAMES[k]: {"launches": int(st.launches[k]), "total_ms": float(st.total_ms[k])}
+        return {KERNEL_NAMES[k]: {"launches": int(st.launches[k]), "total_ms": float(st.total_ms[k]),
+                                 "min_ms": float(st.min_ms[k]), "max_ms": float(st.max_ms[k])}
                 for k in range(IC_K_COUNT)}

@@ -20,6 +20,23 @@
 #include "row_body.h"
 #include "tile_body.h"
 
+#ifndef IC_FUSED_PF
+#define IC_FUSED_PF 1  // row-role tiles prefetched ahead inside the fused kernel
+#endif
+
+#ifdef IC_TRACE2
+extern "C" int ic_debug_dump_phase(long long* host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(ic::tilep::g_phase), 64, 0, hipMemcpyDeviceToHost);
+}
+#endif
+#ifdef IC_TRACE
+// Debug build only: per-workgroup log of (kind, start, end) in 100 MHz ticks.
+__device__ long long g_trace[512 * 128 * 3];
+extern "C" int ic_debug_dump_trace(long long* host, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
+#endif
+
 namespace ic {
 
 namespace {
@@ -44,7 +61,13 @@ __global__ __launch_bounds__(256, 2) void fused_persist_kernel(AttnParams p) {
   int* ctr = p.counters;
   const bool prefer_tile = j >= (gridDim.x >> 4);  // second half of every XCD's workgroups
   bool tile_done = n_t == 0, row_done = n_r == 0;
+#ifdef IC_TRACE
+  int n_ev = 0;
+#endif
   while (!(tile_done && row_done)) {
+#ifdef IC_TRACE
+    const long long t_begin = wall_clock64();
+#endif
     const bool do_tile = tile_done ? false : (row_done ? true : prefer_tile);
     if (threadIdx.x == 0) s_next = atomicAdd(do_tile ? &ctr[x] : &ctr[8], 1);
     __syncthreads();
@@ -63,7 +86,17 @@ __global__ __launch_bounds__(256, 2) void fused_persist_kernel(AttnParams p) {
       rowp::row_body<D, PF, true>(p, it, (int)(idx - item * (uint32_t)H), (float*)lds);
     }
     __syncthreads();  // the bodies leave LDS in use until every wave is through
+#ifdef IC_TRACE
+    if (threadIdx.x == 0 && n_ev < 127) {
+      long long* e = g_trace + ((size_t)blockIdx.x * 128 + n_ev) * 3;
+      e[0] = do_tile ? 1 : 2; e[1] = t_begin; e[2] = wall_clock64();
+      ++n_ev;
+    }
+#endif
   }
+#ifdef IC_TRACE
+  if (threadIdx.x == 0) { long long* e = g_trace + ((size_t)blockIdx.x * 128 + n_ev) * 3; e[0] = 0; e[1] = 0; e[2] = 0; }
+#endif
 }
 
 }  // namespace
@@ -74,8 +107,8 @@ hipError_t launch_fused_kernel(const AttnParams& p, int head_dim, hipStream_t st
   if (slots < 16) return hipErrorInvalidValue;
   const dim3 g((uint32_t)slots), b(256);
   switch (head_dim) {
-    case 64: hipLaunchKernelGGL((fused_persist_kernel<64, 2>), g, b, 0, st, p); break;
-    case 128: hipLaunchKernelGGL((fused_persist_kernel<128, 2>), g, b, 0, st, p); break;
+    case 64: hipLaunchKernelGGL((fused_persist_kernel<64, IC_FUSED_PF>), g, b, 0, st, p); break;
+    case 128: hipLaunchKernelGGL((fused_persist_kernel<128, IC_FUSED_PF>), g, b, 0, st, p); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -14,7 +14,7 @@ using namespace ic;
 namespace {
 
 constexpr int kStagingSlots = 4;       // pinned host buffers cycled by successive calls
-constexpr int kDefaultRowPart = 1024;  // keys per decode work item (512 for head_dim 256)
+constexpr int kDefaultRowPart = 2048;  // keys per decode work item (512 for head_dim 256): ~0.5-1 MiB of KV per head
 constexpr int kDefaultSpanPart = 4096; // keys per span-tile work item
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -138,7 +138,7 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   ps.tile_rows = kTileRows;
   const ic_tuning& t = pool->tune;
   ps.row_part = t.decode_part_tokens > 0 ? round64(t.decode_part_tokens)
-                                         : (pool->cfg.head_dim >= 256 ? kDefaultRowPart / 2 : kDefaultRowPart);
+                                         : (pool->cfg.head_dim >= 256 ? kDefaultRowPart / 4 : kDefaultRowPart);
   ps.row_part = std::min(ps.row_part, kMaxRowPart);
   ps.span_part = t.span_part_tokens > 0 ? round64(t.span_part_tokens) : kDefaultSpanPart;
   ps.spans_as_rows = (t.span_kernel == 1);  // default: MFMA tiles
@@ -549,8 +549,11 @@ int ic_prof_end(ic_pool* pool, ic_prof_stats* out) {
     if (hipEventSynchronize(pr.ev[2 * i + 1]) != hipSuccess) return IC_EHIP;
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, pr.ev[2 * i], pr.ev[2 * i + 1]) != hipSuccess) return IC_EHIP;
-    out->launches[pr.kind[i]] += 1;
-    out->total_ms[pr.kind[i]] += ms;
+    const int k = pr.kind[i];
+    if (out->launches[k] == 0 || ms < out->min_ms[k]) out->min_ms[k] = ms;
+    if (out->launches[k] == 0 || ms > out->max_ms[k]) out->max_ms[k] = ms;
+    out->launches[k] += 1;
+    out->total_ms[k] += ms;
   }
   pr.used = 0;
   return IC_OK;

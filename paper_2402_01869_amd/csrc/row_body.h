@@ -5,13 +5,13 @@
 // Mapping (one workgroup of 4 waves = one RowItem x one head):
 //   - a (block, K or V, head) tile is 16 tokens x D bf16, contiguous; a wave reads it as D/32
 //     loads of 1 KiB, lane l taking bytes [16 l, 16 l + 16): fully coalesced, block-table driven
-//   - a token row is D/8 adjacent lanes, each holding 8 dims; q . k is 8 FMAs per lane and a
-//     D/8-lane all-reduce (DPP inside a 16-lane row)
+//   - a token row is D/8 adjacent lanes, each holding 8 dims; q . k is 4 v_dot2_f32_bf16 per lane
+//     and a D/8-lane all-reduce (DPP inside a 16-lane row)
 //   - every D/8-lane group keeps its own online-softmax state (m, l, acc[8]); groups and waves
 //     are combined once, through LDS, at the end of the item
 //   - wave w owns blocks w, w+4, ... of the item; tiles are register multi-buffered so the
 //     next tiles' loads are in flight while the current one is consumed
-// Scores are kept in log2 units (q is pre-multiplied by scale * log2 e) so exp is one v_exp_f32.
+// Scores are kept in log2 units (multiplied by scale * log2 e) so exp is one v_exp_f32.
 #pragma once
 
 #include "ic_internal.h"
@@ -85,23 +85,27 @@ __device__ __forceinline__ void load_tile(Tile<D>& t, const char* pool, int64_t 
 
 // Consume one 16-token tile.  n_valid < 16 only for the last, partial block of a sequence: its
 // dead slots may hold anything (NaN included), so their score is forced to -inf and their V to 0.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c,
+                                         false);
+}
+
 template <int D, bool MASK>
-__device__ __forceinline__ void consume_tile(const Tile<D>& t, const float (&qf)[8], float& m,
+__device__ __forceinline__ void consume_tile(const Tile<D>& t, const u32x4& q2, float sc, float& m,
                                              float& l, float (&acc)[8], int n_valid, int lane) {
   constexpr int NL = Geo<D>::kLoads;
   float s[NL];
 #pragma unroll
   for (int j = 0; j < NL; ++j) {
+    // q . k over this lane's 8 dims: four bf16-pair dot products with fp32 accumulation
     const u32x4 kk = t.k[j];
-    float d = qf[0] * bf16lo(kk[0]);
-    d = __builtin_fmaf(qf[1], bf16hi(kk[0]), d);
-    d = __builtin_fmaf(qf[2], bf16lo(kk[1]), d);
-    d = __builtin_fmaf(qf[3], bf16hi(kk[1]), d);
-    d = __builtin_fmaf(qf[4], bf16lo(kk[2]), d);
-    d = __builtin_fmaf(qf[5], bf16hi(kk[2]), d);
-    d = __builtin_fmaf(qf[6], bf16lo(kk[3]), d);
-    d = __builtin_fmaf(qf[7], bf16hi(kk[3]), d);
-    s[j] = group_sum<Geo<D>::kLanesPerTok>(d);
+    float d = dot2(q2[0], kk[0], 0.f);
+    d = dot2(q2[1], kk[1], d);
+    d = dot2(q2[2], kk[2], d);
+    d = dot2(q2[3], kk[3], d);
+    s[j] = group_sum<Geo<D>::kLanesPerTok>(d) * sc;
   }
   bool ok[NL];
   float m_new = m;
@@ -161,17 +165,9 @@ __device__ __forceinline__ void row_body(const AttnParams& p, const RowItem& it,
   int my_id = 0;
   if (lane < nb_w) my_id = bt[w + kRowWaves * lane];
 
-  // this lane's 8 query dims, scaled into log2 units
-  float qf[8];
-  {
-    const int d0 = (lane % G::kLanesPerTok) * 8;
-    const u32x4 qq = *(const u32x4*)(p.q + ((int64_t)it.qrow * H + head) * D + d0);
-    const float sc = p.scale_log2e;
-    qf[0] = bf16lo(qq[0]) * sc; qf[1] = bf16hi(qq[0]) * sc;
-    qf[2] = bf16lo(qq[1]) * sc; qf[3] = bf16hi(qq[1]) * sc;
-    qf[4] = bf16lo(qq[2]) * sc; qf[5] = bf16hi(qq[2]) * sc;
-    qf[6] = bf16lo(qq[3]) * sc; qf[7] = bf16hi(qq[3]) * sc;
-  }
+  // this lane's 8 query dims as bf16 pairs; scores are scaled into log2 units after the dot product
+  const u32x4 q2 = *(const u32x4*)(p.q + ((int64_t)it.qrow * H + head) * D + (lane % G::kLanesPerTok) * 8);
+  const float sc = p.scale_log2e;
 
   float m = kNegBig, l = 0.f;
   float acc[8];
@@ -195,9 +191,9 @@ __device__ __forceinline__ void row_body(const AttnParams& p, const RowItem& it,
         const int tok0 = k_begin + (w + kRowWaves * i) * kBlockSize;
         const int n_valid = k_end - tok0;
         if (n_valid >= kBlockSize)
-          consume_tile<D, false>(buf[s], qf, m, l, acc, kBlockSize, lane);
+          consume_tile<D, false>(buf[s], q2, sc, m, l, acc, kBlockSize, lane);
         else
-          consume_tile<D, true>(buf[s], qf, m, l, acc, n_valid, lane);
+          consume_tile<D, true>(buf[s], q2, sc, m, l, acc, n_valid, lane);
       }
     }
   }

@@ -4,17 +4,16 @@
 //
 // One workgroup = one TileItem x one head: up to tile_rows(D) query rows, one wave per 32 rows.
 //   - K and V tiles of 64 keys (4 cache blocks, looked up in the block table) are fetched with
-//     16-byte coalesced loads into registers one tile ahead, then staged in LDS and shared by
+//     16-byte coalesced loads into registers two tiles ahead, then staged in LDS and shared by
 //     the 4 waves.
 //   - S^T = K Q^T: A operand = 32 keys x 16 dims from LDS, B operand = this wave's Q^T kept in
 //     registers for the whole item.  In the 32x32 accumulator layout every lane then owns ONE
 //     query column (lane % 32) and 16 of a subtile's 32 keys, so the online softmax needs a
 //     single cross-lane exchange per tile (with lane ^ 32).
 //   - O^T += V^T P^T: the accumulator registers of S^T, rounded to bf16, already ARE the B
-//     operand (8 keys per lane per MFMA); V is transposed once per workgroup on its way into
-//     LDS, with the keys of each group of 16 stored in the order the accumulator layout yields
-//     them (slot 8*hl + j  <->  key 8*(j/4) + 4*hl + j%4, hl = lane / 32), so the A operand is
-//     one 16-byte LDS read.
+//     operand (8 keys per lane per MFMA, slot j of lane half hl <-> key 8*(j/4) + 4*hl + j%4).
+//     V stays [key][dim] in LDS; the A operand (one dim, 8 keys per lane, in that key order) comes
+//     from two ds_read_b64_tr_b16 transpose loads, so no register transposition is needed.
 //   - Causality: row r of the item sits at position pos0 + r and sees keys <= that position.
 //     Only tiles that straddle a wave's diagonal are masked; tiles beyond it are skipped.
 // Dead slots (keys >= k_end, possibly NaN) get score -inf by select and V = 0 in LDS.
@@ -22,8 +21,15 @@
 
 #include "ic_internal.h"
 
+#ifndef IC_TILE_PIPE
+#define IC_TILE_PIPE 1
+#endif
+
 namespace ic {
 namespace tilep {
+#ifdef IC_TRACE2
+static __device__ long long g_phase[8];
+#endif
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
@@ -45,12 +51,10 @@ struct TW {
 template <int D>
 struct TG {
   static constexpr int kKStride = D + 8;        // bf16 per LDS row of K (16-byte pad)
-  static constexpr int kVStride = kTileK + 8;   // bf16 per LDS row of V^T
+  static constexpr int kVStride = D + 32;       // bf16 per LDS row of V: rows shift by 16 banks
   static constexpr int kChunks = D / 8;         // 16-byte chunks per token row
   static constexpr int kThreads = TW<D>::kThreads;
   static constexpr int kKLoads = kTileK * kChunks / kThreads;      // K chunks per thread
-  static constexpr int kVUnits = 16 * kChunks;                     // (key quad, dim chunk) pairs
-  static constexpr int kVPasses = (kVUnits + kThreads - 1) / kThreads;
   static_assert(kTileK * kChunks % kThreads == 0, "K tile must split evenly over the threads");
   static constexpr int kQSteps = D / 16;        // MFMA k-steps of Q K^T
   static constexpr int kDTiles = D / 32;        // 32-row tiles of O^T
@@ -59,19 +63,12 @@ struct TG {
 template <int D>
 struct Staging {
   u32x4 k[TG<D>::kKLoads];
-  u32x4 v[TG<D>::kVPasses][4];
-};
-
-// Work split of the V tile among threads: unit u = (dim chunk c, key quad tq), tq fastest, so the
-// 64 lanes of a wave cover all 16 key quads of 4 dim chunks.  The transposed 8-byte LDS stores of a
-// wave then fall on distinct banks (measured: the chunk-fastest split is 4-way conflicted).
-template <int D>
-struct VUnit {
-  int tq, c;
-  __device__ __forceinline__ VUnit(int u) : tq(u % 16), c(u / 16) {}
+  u32x4 v[TG<D>::kKLoads];
 };
 
 // Global -> registers for one 64-key tile.  ids = the 4 block ids of the tile (wave-uniform).
+// Thread u takes 16-byte chunk u of the K tile and of the V tile: consecutive lanes read
+// consecutive addresses of a (block, head) tile, so every load instruction is fully coalesced.
 template <int D>
 __device__ __forceinline__ void fetch_tile(Staging<D>& st, const char* pool, const int (&ids)[4],
                                            int head, int H, int tid) {
@@ -79,32 +76,21 @@ __device__ __forceinline__ void fetch_tile(Staging<D>& st, const char* pool, con
   constexpr int kTileBytes = kBlockSize * D * 2;
   const int64_t blk_stride = (int64_t)2 * H * kTileBytes;
   const char* kbase = pool + (int64_t)head * kTileBytes;
-  const char* vbase = kbase + (int64_t)H * kTileBytes;
+  const int64_t v_off = (int64_t)H * kTileBytes;
 #pragma unroll
   for (int j = 0; j < G::kKLoads; ++j) {
-    const int u = tid + G::kThreads * j;    // 16-byte chunk of the K tile
+    const int u = tid + G::kThreads * j;    // 16-byte chunk of the tile
     const int tok = u / G::kChunks;         // 0..63
     const int c = u % G::kChunks;
-    // 256 consecutive chunks never straddle more than one wave-uniform block boundary: tok / 16 is
-    // the same for all lanes of a wave for every supported D
+    // the chunks one wave loads in one instruction never straddle a block: tok / 16 is wave-uniform
     const int bsel = __builtin_amdgcn_readfirstlane(tok / kBlockSize);
-    const int64_t blk = ids[bsel];
-    st.k[j] = *(const u32x4*)(kbase + blk * blk_stride + (tok % kBlockSize) * (D * 2) + c * 16);
-  }
-#pragma unroll
-  for (int ps = 0; ps < G::kVPasses; ++ps) {
-    const int u = tid + G::kThreads * ps;
-    if (u < G::kVUnits) {
-      const VUnit<D> vu(u);
-      const int64_t blk = ids[vu.tq / 4];
-      const char* a = vbase + blk * blk_stride + ((vu.tq % 4) * 4) * (D * 2) + vu.c * 16;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) st.v[ps][i] = *(const u32x4*)(a + i * (D * 2));
-    }
+    const char* a = kbase + (int64_t)ids[bsel] * blk_stride + (tok % kBlockSize) * (D * 2) + c * 16;
+    st.k[j] = *(const u32x4*)a;
+    st.v[j] = *(const u32x4*)(a + v_off);
   }
 }
 
-// Registers -> LDS.  K as is; V transposed (dims become rows); with ZERO, keys >= n_valid are zeroed.
+// Registers -> LDS, both K and V as [key][dim] rows (padded); with ZERO, V of keys >= n_valid is zeroed.
 template <int D, bool ZERO>
 __device__ __forceinline__ void stage_tile(const Staging<D>& st, uint16_t* ks, uint16_t* vs, int tid,
                                            int n_valid) {
@@ -114,35 +100,28 @@ __device__ __forceinline__ void stage_tile(const Staging<D>& st, uint16_t* ks, u
     const int u = tid + G::kThreads * j;
     const int tok = u / G::kChunks, c = u % G::kChunks;
     *(u32x4*)(ks + tok * G::kKStride + c * 8) = st.k[j];
+    u32x4 v = st.v[j];
+    if (ZERO && tok >= n_valid) v = (u32x4){0u, 0u, 0u, 0u};
+    *(u32x4*)(vs + tok * G::kVStride + c * 8) = v;
   }
-#pragma unroll
-  for (int ps = 0; ps < G::kVPasses; ++ps) {
-    const int u = tid + G::kThreads * ps;
-    if (u < G::kVUnits) {
-      const VUnit<D> vu(u);
-      const int tq = vu.tq, c = vu.c;
-      u32x4 r[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        r[i] = st.v[ps][i];
-        if (ZERO && 4 * tq + i >= n_valid) r[i] = (u32x4){0u, 0u, 0u, 0u};
-      }
-      // key quad tq = (group of 16: tq / 4, quad in group: qd): slots 8*(qd % 2) + 4*(qd / 2) ..+3
-      const int qd = tq % 4;
-      const int col = 16 * (tq / 4) + 8 * (qd % 2) + 4 * (qd / 2);
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        // dims 2kk (low halves) and 2kk+1 (high halves) of the 4 keys
-        u32x2 lo, hi;
-        lo[0] = __builtin_amdgcn_perm(r[1][kk], r[0][kk], 0x05040100u);
-        lo[1] = __builtin_amdgcn_perm(r[3][kk], r[2][kk], 0x05040100u);
-        hi[0] = __builtin_amdgcn_perm(r[1][kk], r[0][kk], 0x07060302u);
-        hi[1] = __builtin_amdgcn_perm(r[3][kk], r[2][kk], 0x07060302u);
-        *(u32x2*)(vs + (c * 8 + 2 * kk) * G::kVStride + col) = lo;
-        *(u32x2*)(vs + (c * 8 + 2 * kk + 1) * G::kVStride + col) = hi;
-      }
-    }
-  }
+}
+
+// A operand of O^T += V^T P^T for MFMA rows d = d0 .. d0+31 (this lane: d0 + lane % 32) and the 8 keys
+// of k-step ksp that belong to this lane half, read with the LDS transpose load.  In each group of
+// 16 lanes, lane i supplies the address of an 8-byte row and receives column i % 4 of the rows
+// supplied by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12 (layout measured on gfx950).  So lane j points at
+// V[key j/4][dims 4 (j % 4) ..+3] of its group's 16 dims, and lane i gets V[4 keys][dim i]: two loads
+// give the 8 keys in accumulator order (slots 0-3: keys 4 hl ..+3, slots 4-7: keys 8 + 4 hl ..+3).
+template <int D>
+__device__ __forceinline__ bf16x8 read_vt_operand(const uint16_t* vs, int d0, int ksp, int lane) {
+  using G = TG<D>;
+  typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+  const int hl = lane >> 5;
+  const int j = lane & 15;
+  const uint16_t* a = vs + (16 * ksp + 4 * hl + (j >> 2)) * G::kVStride + d0 + 16 * ((lane & 31) >> 4) + 4 * (j & 3);
+  const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)a);
+  const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(a + 8 * G::kVStride));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
 // One 64-key tile for one wave: S^T = K Q^T, online softmax, O^T += V^T P^T.  mask is set only for
@@ -155,9 +134,32 @@ __device__ __forceinline__ void wave_step(const uint16_t* ks, const uint16_t* vs
   using G = TG<D>;
   f32x16 s_acc[2];
 #pragma unroll
-  for (int tt = 0; tt < 2; ++tt) {
+  for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) s_acc[tt][i] = 0.f;
+#if IC_TILE_PIPE
+  // Both 32-key subtiles advance together (two independent accumulators alternate in the MFMA
+  // pipe) and the A operands of the next k-step are read from LDS before this step's MFMAs issue.
+  {
+    const uint16_t* kp0 = ks + col * G::kKStride + 8 * hl;
+    const uint16_t* kp1 = kp0 + 32 * G::kKStride;
+    bf16x8 a0 = *(const bf16x8*)kp0, a1 = *(const bf16x8*)kp1;
+#pragma unroll
+    for (int s = 0; s < G::kQSteps; ++s) {
+      bf16x8 n0 = a0, n1 = a1;
+      if (s + 1 < G::kQSteps) {
+        n0 = *(const bf16x8*)(kp0 + 16 * (s + 1));
+        n1 = *(const bf16x8*)(kp1 + 16 * (s + 1));
+      }
+      s_acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[s], s_acc[0], 0, 0, 0);
+      s_acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[s], s_acc[1], 0, 0, 0);
+      a0 = n0;
+      a1 = n1;
+    }
+  }
+#else
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt) {
     const uint16_t* kp = ks + (32 * tt + col) * G::kKStride + 8 * hl;
 #pragma unroll
     for (int s = 0; s < G::kQSteps; ++s) {
@@ -165,6 +167,7 @@ __device__ __forceinline__ void wave_step(const uint16_t* ks, const uint16_t* vs
       s_acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], s_acc[tt], 0, 0, 0);
     }
   }
+#endif
   // Scores stay unscaled in the accumulators; the scale (> 0, in log2 units) is folded into the
   // exponent: p = 2^(s*sc - m).
   if (mask) {  // wave-uniform; the empty asm keeps this a branch instead of 32 always-on selects
@@ -204,20 +207,41 @@ __device__ __forceinline__ void wave_step(const uint16_t* ks, const uint16_t* vs
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc_o[dt][i] *= alpha;
   }
+#if IC_TILE_PIPE
+  // O^T += V^T P^T, k-step outer so that the kDTiles independent accumulators alternate
+  {
+    const int lane = col + 32 * hl;
+    bf16x8 a[G::kDTiles];
 #pragma unroll
-  for (int dt = 0; dt < G::kDTiles; ++dt) {
-    const uint16_t* vp = vs + (32 * dt + col) * G::kVStride + 8 * hl;
+    for (int dt = 0; dt < G::kDTiles; ++dt) a[dt] = read_vt_operand<D>(vs, 32 * dt, 0, lane);
 #pragma unroll
     for (int ksp = 0; ksp < 4; ++ksp) {
-      const bf16x8 a = *(const bf16x8*)(vp + 16 * ksp);
+      bf16x8 n[G::kDTiles];
+#pragma unroll
+      for (int dt = 0; dt < G::kDTiles; ++dt)
+        n[dt] = ksp + 1 < 4 ? read_vt_operand<D>(vs, 32 * dt, ksp + 1, lane) : a[dt];
+#pragma unroll
+      for (int dt = 0; dt < G::kDTiles; ++dt)
+        acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[dt], pb[ksp], acc_o[dt], 0, 0, 0);
+#pragma unroll
+      for (int dt = 0; dt < G::kDTiles; ++dt) a[dt] = n[dt];
+    }
+  }
+#else
+#pragma unroll
+  for (int dt = 0; dt < G::kDTiles; ++dt) {
+#pragma unroll
+    for (int ksp = 0; ksp < 4; ++ksp) {
+      const bf16x8 a = read_vt_operand<D>(vs, 32 * dt, ksp, col + 32 * hl);
       acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ksp], acc_o[dt], 0, 0, 0);
     }
   }
+#endif
 }
 
 template <int D>
 constexpr int tile_lds_bytes() {
-  return (kTileK * TG<D>::kKStride + D * TG<D>::kVStride) * 2;
+  return (kTileK * TG<D>::kKStride + kTileK * TG<D>::kVStride) * 2;
 }
 
 // One TileItem x one head, executed by a workgroup of tile_rows(D) / 32 waves.
@@ -268,29 +292,68 @@ __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& i
     for (int i = 0; i < 4; ++i) ids[i] = bt[min(b0 + i, last_blk)];
   };
 
-  Staging<D> st;
-  int ids_cur[4], ids_nxt[4];
-  tile_ids(0, ids_cur);
-  fetch_tile<D>(st, pool, ids_cur, head, H, tid);
-  if (n_tiles > 1) tile_ids(1, ids_nxt);
-
-  for (int t = 0; t < n_tiles; ++t) {
+  // Key tiles are fetched PFD tiles ahead into PFD register sets: one tile of compute (about 2000
+  // cycles) does not cover an HBM round trip under load, two do.  ids_nxt always holds the block
+  // ids of the tile that the next fetch will read, loaded one step before they are needed.
+  constexpr int PFD = D <= 128 ? 2 : 1;  // head_dim 256 has no registers for a second staging set
+#ifdef IC_TRACE2
+  long long ph[6] = {0, 0, 0, 0, 0, 0};
+#define IC_PH(i) { const long long now_ = clock64(); ph[i] += now_ - last_; last_ = now_; }
+#else
+#define IC_PH(i)
+#endif
+  auto step = [&](int t, Staging<D>& st, int (&ids_nxt)[4]) {
+#ifdef IC_TRACE2
+    long long last_ = clock64();
+#endif
     const int kt = it.k_begin + t * kTileK;
     if (it.k_end - kt >= kTileK)
       stage_tile<D, false>(st, ks, vs, tid, kTileK);
     else
       stage_tile<D, true>(st, ks, vs, tid, it.k_end - kt);
+    IC_PH(0)
     __syncthreads();
-    if (t + 1 < n_tiles) {
+    IC_PH(1)
+    if (t + PFD < n_tiles) {
       fetch_tile<D>(st, pool, ids_nxt, head, H, tid);
-      if (t + 2 < n_tiles) tile_ids(t + 2, ids_nxt);
+      if (t + PFD + 1 < n_tiles) tile_ids(t + PFD + 1, ids_nxt);
     }
+    IC_PH(2)
     if (kt <= wave_pos_hi) {  // otherwise every key of the tile is in this wave's future
       wave_step<D>(ks, vs, qreg, acc_o, m, l, kt, pos, col, hl, sc, kt + kTileK - 1 > wave_pos_lo);
     }
+    IC_PH(3)
     __syncthreads();
+    IC_PH(4)
+  };
+
+  int ids[4];
+  tile_ids(0, ids);
+  if constexpr (PFD == 2) {
+    Staging<D> st0, st1;
+    fetch_tile<D>(st0, pool, ids, head, H, tid);
+    if (n_tiles > 1) {
+      tile_ids(1, ids);
+      fetch_tile<D>(st1, pool, ids, head, H, tid);
+    }
+    if (n_tiles > 2) tile_ids(2, ids);
+    for (int t = 0; t < n_tiles; t += 2) {
+      step(t, st0, ids);
+      if (t + 1 < n_tiles) step(t + 1, st1, ids);
+    }
+  } else {
+    Staging<D> st0;
+    fetch_tile<D>(st0, pool, ids, head, H, tid);
+    if (n_tiles > 1) tile_ids(1, ids);
+    for (int t = 0; t < n_tiles; ++t) step(t, st0, ids);
   }
 
+#ifdef IC_TRACE2
+  if (lane == 0) {
+    for (int i = 0; i < 5; ++i) atomicAdd((unsigned long long*)&g_phase[i], (unsigned long long)ph[i]);
+    atomicAdd((unsigned long long*)&g_phase[5], (unsigned long long)n_tiles);
+  }
+#endif
   // ---- epilogue: lane holds O^T[d][col] for d = 32 dt + 8 (i/4) + 4 hl + i%4
   l += __shfl_xor(l, 32);
   if (row_ok) {
