@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--span-kernel", type=int, default=0)
     ap.add_argument("--row-variant", type=int, default=0)
     ap.add_argument("--serial-spans", type=int, default=0)
+    ap.add_argument("--row-launch", type=int, default=0)
+    ap.add_argument("--row-slots", type=int, default=0)
     ap.add_argument("--no-swap", action="store_true", help="time the attention call only")
     ap.add_argument("--decode-only", action="store_true", help="drop the recomputation spans from the batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -120,7 +122,7 @@ def main():
     pool_t = torch.empty(W.pool_shape(acfg.pool_blocks, H, 16, D), dtype=torch.bfloat16, device=dev)
     W.fill_pool_device_normal(pool_t, acfg.seed)
     pool = B.KvPool.from_tensor(pool_t, H, D)
-    pool.set_tuning(args.decode_part, args.span_part, args.span_kernel, args.row_variant, args.serial_spans)
+    pool.set_tuning(args.decode_part, args.span_part, args.span_kernel, args.row_variant, args.serial_spans, args.row_launch, args.row_slots)
     batches = [W.make_batch(acfg, acfg.seed), W.make_batch(acfg, acfg.seed + 1000)]
     descs, qs, outs = [], [], []
     ws_bytes = 0
@@ -213,7 +215,7 @@ def main():
     if prof["fused"]["launches"]:
         dom, dom_name, dom_bytes = "fused", "fused_persist_kernel", kv_bytes
     else:
-        dom, dom_name = "row", "row_attn_kernel"
+        dom, dom_name = "row", ("row_attn_kernel" if args.row_launch == 1 else "row_persist_kernel")
         dom_bytes = kv_bytes if plan["tile_items"] == 0 else dec_bytes
     if prof[dom]["launches"]:
         ach = dom_bytes / (avg_ms(dom) * 1e-3) / 1e9

@@ -132,7 +132,10 @@ typedef struct {
   int32_t row_variant;        /* vector-kernel build: bit 0 = prefetch two tiles ahead, bit 1 = cached (not non-temporal) KV loads */
   int32_t serial_spans;       /* 1 = run span tiles and decode rows as two kernels, one after the other,
                                  instead of one fused launch                                 */
-  int32_t reserved[3];        /* must be 0                                                   */
+  int32_t row_launch;         /* single-role row kernel: 0 = built-in choice (persistent, one workgroup per CU),
+                                 1 = one workgroup per work item, 2 = persistent               */
+  int32_t row_slots;          /* resident workgroups of the persistent row kernel; 0 = one per CU */
+  int32_t reserved[1];        /* must be 0                                                   */
 } ic_tuning;
 int ic_pool_set_tuning(ic_pool* pool, const ic_tuning* tuning);
 

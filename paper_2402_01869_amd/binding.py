@@ -49,7 +49,7 @@ class BatchDesc(C.Structure):
 
 class Tuning(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("decode_part_tokens", "span_part_tokens", "span_kernel", "row_variant",
-                                         "serial_spans")] + [("reserved", C.c_int32 * 3)]
+                                         "serial_spans", "row_launch", "row_slots")] + [("reserved", C.c_int32 * 1)]
 
 
 class PlanInfo(C.Structure):
@@ -182,9 +182,10 @@ class KvPool:
     def block_bytes(self) -> int:
         return int(lib().kv_block_bytes(self._h))
 
-    def set_tuning(self, decode_part_tokens=0, span_part_tokens=0, span_kernel=0, row_variant=0, serial_spans=0):
+    def set_tuning(self, decode_part_tokens=0, span_part_tokens=0, span_kernel=0, row_variant=0, serial_spans=0,
+                   row_launch=0, row_slots=0):
         t = Tuning(int(decode_part_tokens), int(span_part_tokens), int(span_kernel), int(row_variant),
-                   int(serial_spans), (C.c_int32 * 3)(0, 0, 0))
+                   int(serial_spans), int(row_launch), int(row_slots), (C.c_int32 * 1)(0))
         rc = lib().ic_pool_set_tuning(self._h, C.byref(t))
         if rc != IC_OK:
             raise InferceptError(rc, "ic_pool_set_tuning")

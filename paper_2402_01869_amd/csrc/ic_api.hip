@@ -371,8 +371,8 @@ int ic_pool_set_tuning(ic_pool* pool, const ic_tuning* tuning) {
   if (!pool || !tuning) return IC_ENULL;
   if (tuning->decode_part_tokens < 0 || tuning->span_part_tokens < 0 || tuning->span_kernel < 0 ||
       tuning->span_kernel > 2 || tuning->row_variant < 0 || tuning->row_variant > 3 ||
-      tuning->serial_spans < 0 || tuning->serial_spans > 1 || tuning->reserved[0] || tuning->reserved[1] ||
-      tuning->reserved[2])
+      tuning->serial_spans < 0 || tuning->serial_spans > 1 || tuning->row_launch < 0 || tuning->row_launch > 2 ||
+      tuning->row_slots < 0 || tuning->row_slots > 65536 || tuning->reserved[0])
     return IC_EINVAL;
   pool->tune = *tuning;
   return IC_OK;
@@ -459,7 +459,10 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
     }
     if (p.n_row_items > 0) {
       ProfScope ps_(pool, IC_K_ROW, st);
-      if (launch_row_kernel(p, D, st) != hipSuccess) return IC_EHIP;
+      const int slots = pool->tune.row_slots > 0 ? pool->tune.row_slots : pool->num_cus;
+      const hipError_t e = pool->tune.row_launch != 1 ? launch_row_persist(p, D, slots, st)
+                                                      : launch_row_kernel(p, D, st);
+      if (e != hipSuccess) return IC_EHIP;
     }
   }
   if (p.n_merge_items > 0) {

@@ -69,6 +69,7 @@ struct AttnParams {
 
 // Launchers (defined next to their kernels).  Each returns a hipError_t.
 hipError_t launch_row_kernel(const AttnParams& p, int head_dim, hipStream_t st);
+hipError_t launch_row_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st);
 hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_merge_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_fused_kernel(const AttnParams& p, int head_dim, hipStream_t st);
