@@ -29,8 +29,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="mixed_13b", choices=["mixed_13b", "gptj_decode", "long_ctx", "tiny"])
     ap.add_argument("--decode-part", type=int, default=0)
     ap.add_argument("--span-part", type=int, default=0)
@@ -163,27 +163,46 @@ def main():
             spool.kv_pack_blocks(src, stagings[k].data_ptr(), sbytes, stream)
             spool.kv_unpack_blocks(dst, stagings[k ^ 1].data_ptr(), sbytes, stream)
 
+    # Per-kernel HIP events are created now (and switched off again) so that nothing but a
+    # synchronize sits between the loops below: an idle gap lets the GPU clocks drop, and the first
+    # ~20 ms after it run up to 20 % slower.
+    pool.prof_begin(8 * args.steps + 8)
+    pool.prof_end()
+    if do_swap:
+        spool.prof_begin(4 * args.steps + 8)
+        spool.prof_end()
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
 
-    pool.prof_begin(8 * args.steps + 8)
-    if do_swap:
-        spool.prof_begin(4 * args.steps + 8)
-    torch.cuda.synchronize()
+    # ---- loop 1: EXACTLY K steps, nothing but the three calls per step -> ms_per_step, value
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # ---- loop 2: K more steps with a HIP event pair around every kernel, recorded by the library on
+    # the stream each kernel is launched on -> average launch durations for the roofline
+    pool.prof_begin(8 * args.steps + 8)
+    if do_swap:
+        spool.prof_begin(4 * args.steps + 8)
+    tp = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step_events = (time.perf_counter() - tp) * 1e3 / args.steps
     prof = pool.prof_end()
     if do_swap:
         sp = spool.prof_end()
         prof["pack"], prof["unpack"] = sp["pack"], sp["unpack"]
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-    # wall time of the attention call alone (same inputs, separate loop; kernels may overlap inside it)
+    # ---- loop 3: wall time of the attention call alone (kernels overlap inside it)
+    for i in range(min(10, args.steps)):
+        k = i & 1
+        pool.paged_attn_mixed(descs[k], qs[k][0].data_ptr(), outs[k].data_ptr(), ws.data_ptr(), ws.numel(), stream)
     torch.cuda.synchronize()
     ta = time.perf_counter()
     for i in range(args.steps):
@@ -191,6 +210,7 @@ def main():
         pool.paged_attn_mixed(descs[k], qs[k][0].data_ptr(), outs[k].data_ptr(), ws.data_ptr(), ws.numel(), stream)
     torch.cuda.synchronize()
     attn_wall_ms = (time.perf_counter() - ta) * 1e3 / args.steps
+
     kv_bytes = float(np.mean([b.kv_bytes() for b in batches]))
     dec_bytes = float(np.mean([int(b.ctx_len[b.q_len == 1].astype(np.int64).sum()) * b.token_bytes for b in batches]))
     span_flops = float(np.mean([b.span_flops() for b in batches]))
@@ -201,29 +221,30 @@ def main():
         return prof[k]["total_ms"] / prof[k]["launches"] if prof[k]["launches"] else None
 
     plan = pool.plan_query(descs[0])
-    attn_ms = sum((avg_ms(k) or 0.0) * (prof[k]["launches"] / args.steps) for k in ("row", "tile", "merge", "fused"))
+    attn_ms = sum((avg_ms(k) or 0.0) * (prof[k]["launches"] / args.steps) for k in ("row", "tile", "merge"))
     kernels = {}
-    for k in ("row", "tile", "merge", "fused", "pack", "unpack"):
+    for k in ("row", "tile", "merge", "pack", "unpack"):
         if prof[k]["launches"]:
             kernels[k] = {"launches": prof[k]["launches"], "avg_ms": round(avg_ms(k), 5),
                           "min_ms": round(prof[k]["min_ms"], 5), "max_ms": round(prof[k]["max_ms"], 5)}
 
-    # Dominant kernel of the step: the fused mixed kernel when the batch has spans and decode rows
-    # (it moves every KV byte of the call once), else the row kernel (decode rows only).
-    # Algorithmic bytes per launch = KV bytes of the rows it is handed, each context counted once.
+    # Dominant kernel of the step: the row kernel (decode rows, HBM-bound).  In a mixed batch it runs
+    # beside the tile kernel, which reads the spans' keys at the same time; its own algorithmic bytes
+    # are the decode sequences' KV, each context once (all KV bytes if spans run row by row).
     roofline = None
-    if prof["fused"]["launches"]:
-        dom, dom_name, dom_bytes = "fused", "fused_persist_kernel", kv_bytes
-    else:
-        dom, dom_name = "row", ("row_attn_kernel" if args.row_launch == 1 else "row_persist_kernel")
+    if prof["row"]["launches"]:
         dom_bytes = kv_bytes if plan["tile_items"] == 0 else dec_bytes
-    if prof[dom]["launches"]:
-        ach = dom_bytes / (avg_ms(dom) * 1e-3) / 1e9
-        roofline = {"kernel": dom_name, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+        ach = dom_bytes / (avg_ms("row") * 1e-3) / 1e9
+        beside = prof["tile"]["launches"] > 0 and not args.serial_spans and D <= 128
+        name = ("row_persist_slim_kernel" if beside else
+                "row_attn_kernel" if args.row_launch == 1 else "row_persist_kernel")
+        roofline = {"kernel": name, "runs_beside": "tile_persist_kernel" if beside else None,
+                    "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
-                    "traffic": (MEASURED_TRAFFIC_BYTES.get(f"{args.workload}/{dom}")
-                                if not (args.decode_only or args.decode_part or args.span_part) else None),
-                    "bytes_per_launch": dom_bytes, "avg_launch_ms": round(avg_ms(dom), 5)}
+                    "traffic": (MEASURED_TRAFFIC_BYTES.get(f"{args.workload}/row")
+                                if not (args.decode_only or args.decode_part or args.span_part or args.serial_spans)
+                                else None),
+                    "bytes_per_launch": dom_bytes, "avg_launch_ms": round(avg_ms("row"), 5)}
 
     result = {
         "metric": "mixed paged-attn KV-read GB/s (% HBM peak); swap pack/unpack GB/s",
@@ -232,6 +253,7 @@ def main():
         "value_definition": "algorithmic bytes of one step (KV bytes read once per sequence + pack read+write + "
                             "unpack read+write) / wall time of the step",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_with_kernel_events": round(ms_per_step_events, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{acfg.name} attention ({acfg.n_decode} decode + {acfg.n_span}x{acfg.span_len}-row spans, "

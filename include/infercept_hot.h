@@ -130,8 +130,8 @@ typedef struct {
   int32_t span_part_tokens;   /* keys per work item of a span's query tile                   */
   int32_t span_kernel;        /* 0 = built-in choice, 1 = row-by-row vector kernel, 2 = MFMA tiles */
   int32_t row_variant;        /* vector-kernel build: bit 0 = prefetch two tiles ahead, bit 1 = cached (not non-temporal) KV loads */
-  int32_t serial_spans;       /* 1 = run span tiles and decode rows as two kernels, one after the other,
-                                 instead of one fused launch                                 */
+  int32_t serial_spans;       /* 1 = run the span kernel, then the row kernel, on the caller's stream instead of
+                                 two persistent kernels side by side (the tile kernel on the pool's own stream) */
   int32_t row_launch;         /* single-role row kernel: 0 = built-in choice (persistent, one workgroup per CU),
                                  1 = one workgroup per work item, 2 = persistent               */
   int32_t row_slots;          /* resident workgroups of the persistent row kernel; 0 = one per CU */
@@ -174,7 +174,7 @@ int ic_check_ids(const ic_pool_cfg* cfg, const int32_t* host_ids, int32_t n, int
  * ic_prof_begin and ic_prof_end every kernel the pool launches is bracketed by an event pair.
  * ic_prof_end synchronises the recorded events and returns totals per kernel kind.
  * ------------------------------------------------------------------------------------------ */
-enum { IC_K_ROW = 0, IC_K_TILE = 1, IC_K_MERGE = 2, IC_K_PACK = 3, IC_K_UNPACK = 4, IC_K_FUSED = 5, IC_K_COUNT = 6 };
+enum { IC_K_ROW = 0, IC_K_TILE = 1, IC_K_MERGE = 2, IC_K_PACK = 3, IC_K_UNPACK = 4, IC_K_COUNT = 5 };
 typedef struct {
   int32_t launches[IC_K_COUNT];
   float total_ms[IC_K_COUNT];

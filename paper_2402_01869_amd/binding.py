@@ -19,8 +19,8 @@ IC_OK = 0
 IC_ENULL, IC_EINVAL, IC_ERANGE, IC_ESIZE, IC_EALIGN = -1, -2, -3, -4, -5
 IC_EDUP, IC_EUNSUPPORTED, IC_EOVERLAP, IC_EHIP, IC_ENOMEM = -6, -7, -8, -9, -10
 IC_FLAG_TRUSTED = 1
-IC_K_ROW, IC_K_TILE, IC_K_MERGE, IC_K_PACK, IC_K_UNPACK, IC_K_FUSED, IC_K_COUNT = 0, 1, 2, 3, 4, 5, 6
-KERNEL_NAMES = ("row", "tile", "merge", "pack", "unpack", "fused")
+IC_K_ROW, IC_K_TILE, IC_K_MERGE, IC_K_PACK, IC_K_UNPACK, IC_K_COUNT = 0, 1, 2, 3, 4, 5
+KERNEL_NAMES = ("row", "tile", "merge", "pack", "unpack")
 
 EXPORTS = (
     "ic_strerror", "kv_pool_init", "kv_pool_destroy", "kv_block_bytes",

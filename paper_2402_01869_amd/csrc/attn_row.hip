@@ -90,6 +90,28 @@ hipError_t launch_row_kernel(const AttnParams& p, int head_dim, hipStream_t st) 
   return hipGetLastError();
 }
 
+// Slim build of the persistent row kernel for running BESIDE the tile kernel: no register prefetch
+// (measured not to matter there: the CU's memory pipe, not the wave, holds the loads in flight)
+// and at most 80 VGPRs, so that one of these workgroups fits on a CU next to a tile workgroup.
+template <int D>
+__global__ __launch_bounds__(kRowWaves * 64, 6) void row_persist_slim_kernel(AttnParams p) {
+  __shared__ __attribute__((aligned(16))) float lds[row_lds_bytes<D>() / sizeof(float)];
+  __shared__ int s_next;
+  const int H = p.num_heads;
+  const uint32_t n_r = (uint32_t)p.n_row_items * (uint32_t)H;
+  for (;;) {
+    if (threadIdx.x == 0) s_next = atomicAdd(&p.counters[8], 1);
+    __syncthreads();
+    const uint32_t idx = (uint32_t)s_next;
+    __syncthreads();
+    if (idx >= n_r) break;
+    const uint32_t item = idx / (uint32_t)H;
+    const RowItem it = p.row_items[item];
+    row_body<D, 0, true>(p, it, (int)(idx - item * (uint32_t)H), lds);
+    __syncthreads();
+  }
+}
+
 hipError_t launch_row_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st) {
   if (p.n_row_items <= 0) return hipSuccess;
   if (!p.counters || slots < 1) return hipErrorInvalidValue;
@@ -98,6 +120,18 @@ hipError_t launch_row_persist(const AttnParams& p, int head_dim, int slots, hipS
     case 64: hipLaunchKernelGGL((row_persist_kernel<64, 1>), g, b, 0, st, p); break;
     case 128: hipLaunchKernelGGL((row_persist_kernel<128, 1>), g, b, 0, st, p); break;
     case 256: hipLaunchKernelGGL((row_persist_kernel<256, 1>), g, b, 0, st, p); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_row_persist_slim(const AttnParams& p, int head_dim, int slots, hipStream_t st) {
+  if (p.n_row_items <= 0) return hipSuccess;
+  if (!p.counters || slots < 1) return hipErrorInvalidValue;
+  const dim3 g((uint32_t)slots), b(kRowWaves * 64);
+  switch (head_dim) {
+    case 64: hipLaunchKernelGGL(row_persist_slim_kernel<64>, g, b, 0, st, p); break;
+    case 128: hipLaunchKernelGGL(row_persist_slim_kernel<128>, g, b, 0, st, p); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

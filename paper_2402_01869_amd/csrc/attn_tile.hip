@@ -18,6 +18,34 @@ __global__ __launch_bounds__(TW<D>::kThreads, (D <= 128 ? 2 : 1)) void tile_attn
   tile_body<D>(p, it, head, lds);
 }
 
+// Persistent launch of the same body, for running beside the row kernel: `slots` workgroups (one
+// per CU; two do not fit) pull tile items from one queue per XCD with atomic counters
+// (counters[0..7], zeroed by the descriptor upload).  Workgroups are dealt round-robin to the 8 XCDs
+// (L2 domains) by block index, so XCD x = index % 8 owns the tile items of the heads h = x (mod 8),
+// in head-major order: the query tiles of one (sequence, head), which read the same keys, run on
+// one L2 at the same time, and each span's keys are fetched from HBM about once.
+template <int D>
+__global__ __launch_bounds__(TW<D>::kThreads, (D <= 128 ? 2 : 1)) void tile_persist_kernel(AttnParams p) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[tile_lds_bytes<D>() / 2];
+  __shared__ int s_next;
+  const int H = p.num_heads;
+  const uint32_t x = blockIdx.x & 7u;
+  const uint32_t heads_x = (uint32_t)(H - (int)x + 7) / 8u;  // heads congruent to x mod 8
+  const uint32_t n_t = (uint32_t)p.n_tile_items * heads_x;
+  for (;;) {
+    if (threadIdx.x == 0) s_next = atomicAdd(&p.counters[x], 1);
+    __syncthreads();
+    const uint32_t idx = (uint32_t)s_next;
+    __syncthreads();  // s_next is rewritten at the top of the next round
+    if (idx >= n_t) break;
+    const uint32_t hsel = idx / (uint32_t)p.n_tile_items;
+    const uint32_t item = idx - hsel * (uint32_t)p.n_tile_items;
+    const TileItem it = p.tile_items[item];
+    tile_body<D>(p, it, (int)(x + 8u * hsel), lds);
+    __syncthreads();  // the body leaves LDS in use until every wave is through
+  }
+}
+
 }  // namespace
 
 hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st) {
@@ -29,6 +57,19 @@ hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st)
     case 64: hipLaunchKernelGGL(tile_attn_kernel<64>, g, dim3(TW<64>::kThreads), 0, st, p); break;
     case 128: hipLaunchKernelGGL(tile_attn_kernel<128>, g, dim3(TW<128>::kThreads), 0, st, p); break;
     case 256: hipLaunchKernelGGL(tile_attn_kernel<256>, g, dim3(TW<256>::kThreads), 0, st, p); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+// slots is rounded down to a multiple of 8 so that every XCD gets the same number of workgroups.
+hipError_t launch_tile_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st) {
+  if (p.n_tile_items <= 0) return hipSuccess;
+  if (!p.counters || slots < 8) return hipErrorInvalidValue;
+  const dim3 g((uint32_t)(slots - slots % 8));
+  switch (head_dim) {
+    case 64: hipLaunchKernelGGL(tile_persist_kernel<64>, g, dim3(TW<64>::kThreads), 0, st, p); break;
+    case 128: hipLaunchKernelGGL(tile_persist_kernel<128>, g, dim3(TW<128>::kThreads), 0, st, p); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -15,7 +15,7 @@ namespace {
 
 constexpr int kStagingSlots = 4;       // pinned host buffers cycled by successive calls
 constexpr int kDefaultRowPart = 2048;  // keys per decode work item (512 for head_dim 256): ~0.5-1 MiB of KV per head
-constexpr int kDefaultSpanPart = 4096; // keys per span-tile work item
+constexpr int kDefaultSpanPart = 8192; // keys per span-tile work item (partials of 256 rows are costly)
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -47,6 +47,8 @@ struct ic_pool {
   int32_t* dev_ids;
   size_t dev_ids_cap;
   int num_cus;           // compute units of the pool's device (0 until the first attention call)
+  hipStream_t side;      // second stream: the tile kernel runs beside the row kernel
+  hipEvent_t ev_fork, ev_join;
   ProfState prof;
 };
 
@@ -335,6 +337,8 @@ int kv_pool_init(const ic_pool_cfg* cfg, void* dev_pool_base, size_t pool_bytes,
   p->dev_ids = nullptr;
   p->dev_ids_cap = 0;
   p->num_cus = 0;
+  p->side = nullptr;
+  p->ev_fork = p->ev_join = nullptr;
   *out = p;
   return IC_OK;
 }
@@ -349,6 +353,12 @@ int kv_pool_destroy(ic_pool* pool) {
   }
   for (hipEvent_t e : pool->prof.ev) (void)hipEventDestroy(e);
   if (pool->dev_ids) (void)hipFree(pool->dev_ids);
+  if (pool->side) {
+    if (hipStreamSynchronize(pool->side) != hipSuccess) rc = IC_EHIP;
+    (void)hipStreamDestroy(pool->side);
+  }
+  if (pool->ev_fork) (void)hipEventDestroy(pool->ev_fork);
+  if (pool->ev_join) (void)hipEventDestroy(pool->ev_join);
   delete pool;
   return rc;
 }
@@ -371,7 +381,7 @@ int ic_pool_set_tuning(ic_pool* pool, const ic_tuning* tuning) {
   if (!pool || !tuning) return IC_ENULL;
   if (tuning->decode_part_tokens < 0 || tuning->span_part_tokens < 0 || tuning->span_kernel < 0 ||
       tuning->span_kernel > 2 || tuning->row_variant < 0 || tuning->row_variant > 3 ||
-      tuning->serial_spans < 0 || tuning->serial_spans > 1 || tuning->row_launch < 0 || tuning->row_launch > 2 ||
+      tuning->serial_spans < 0 || tuning->serial_spans > 1 || tuning->row_launch < 0 || tuning->row_launch > 3 ||
       tuning->row_slots < 0 || tuning->row_slots > 65536 || tuning->reserved[0])
     return IC_EINVAL;
   pool->tune = *tuning;
@@ -442,16 +452,32 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
   p.n_merge_items = ps.info.merge_rows;
   p.scale_log2e = desc->scale * 1.4426950408889634f;
   p.row_variant = pool->tune.row_variant;
-  p.persist_slots = pool->num_cus * 2;
   p.counters = (int32_t*)(ws + ps.off_ctr);
 
-  // Decode rows are HBM-bound and span tiles are MFMA-bound (the complementarity Section 4.2
-  // builds on): a batch that has both runs them in one fused launch that co-schedules the two
-  // roles on every CU.  serial_spans = 1 keeps the two single-role kernels, one after the other.
-  const bool fused = p.n_tile_items > 0 && p.n_row_items > 0 && !pool->tune.serial_spans && D <= 128;
-  if (fused) {
-    ProfScope ps_(pool, IC_K_FUSED, st);
-    if (launch_fused_kernel(p, D, st) != hipSuccess) return IC_EHIP;
+  // Decode rows are memory-bound and span tiles are MFMA-bound (the complementarity Section 4.2
+  // builds on): a batch that has both runs them as two persistent kernels side by side, one
+  // workgroup of each per CU, the tile kernel on the pool's second stream (forked from and joined
+  // back into the caller's stream by events).  serial_spans = 1, and head_dim 256 (whose tile
+  // workgroup leaves no registers for a neighbour), run one kernel after the other instead.
+  const bool beside = p.n_tile_items > 0 && p.n_row_items > 0 && !pool->tune.serial_spans && D <= 128;
+  if (beside) {
+    if (!pool->side) {
+      if (hipStreamCreateWithFlags(&pool->side, hipStreamNonBlocking) != hipSuccess) return IC_EHIP;
+      if (hipEventCreateWithFlags(&pool->ev_fork, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
+      if (hipEventCreateWithFlags(&pool->ev_join, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
+    }
+    if (hipEventRecord(pool->ev_fork, st) != hipSuccess) return IC_EHIP;
+    if (hipStreamWaitEvent(pool->side, pool->ev_fork, 0) != hipSuccess) return IC_EHIP;
+    {
+      ProfScope ps_(pool, IC_K_TILE, pool->side);
+      if (launch_tile_persist(p, D, pool->num_cus, pool->side) != hipSuccess) return IC_EHIP;
+    }
+    if (hipEventRecord(pool->ev_join, pool->side) != hipSuccess) return IC_EHIP;
+    {
+      ProfScope ps_(pool, IC_K_ROW, st);
+      if (launch_row_persist_slim(p, D, pool->num_cus, st) != hipSuccess) return IC_EHIP;
+    }
+    if (hipStreamWaitEvent(st, pool->ev_join, 0) != hipSuccess) return IC_EHIP;
   } else {
     if (p.n_tile_items > 0) {
       ProfScope ps_(pool, IC_K_TILE, st);
@@ -460,8 +486,9 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
     if (p.n_row_items > 0) {
       ProfScope ps_(pool, IC_K_ROW, st);
       const int slots = pool->tune.row_slots > 0 ? pool->tune.row_slots : pool->num_cus;
-      const hipError_t e = pool->tune.row_launch != 1 ? launch_row_persist(p, D, slots, st)
-                                                      : launch_row_kernel(p, D, st);
+      const hipError_t e = pool->tune.row_launch == 3 && D <= 128 ? launch_row_persist_slim(p, D, slots, st)
+                           : pool->tune.row_launch != 1       ? launch_row_persist(p, D, slots, st)
+                                                              : launch_row_kernel(p, D, st);
       if (e != hipSuccess) return IC_EHIP;
     }
   }

@@ -12,7 +12,7 @@ constexpr int kRowWaves = 4;    // waves per workgroup of the row kernel
 constexpr int kMaxRowPart = 4096;  // keys per row-kernel work item: 64 block ids per wave
 
 // Query rows per work item of the MFMA tile kernel (planner and kernel must agree).
-constexpr int tile_rows(int head_dim) { return head_dim > 0 ? 128 : 128; }
+constexpr int tile_rows(int head_dim) { return head_dim <= 128 ? 256 : 128; }
 
 // One work item of the row kernel: one query row against keys [k_begin, k_end) of its sequence,
 // for every head (the head is a grid dimension).  32 bytes so a wave reads it with scalar loads.
@@ -63,16 +63,16 @@ struct AttnParams {
   int32_t n_merge_items;
   float scale_log2e;       // scale * log2(e): scores are kept in log2 units
   int32_t row_variant;     // row-kernel build: bit0 = prefetch depth 2, bit1 = plain (cached) loads
-  int32_t persist_slots;   // fused kernel: resident workgroups (2 per CU)
   int32_t* counters;       // 16 work-queue counters, zero when the kernel starts
 };
 
 // Launchers (defined next to their kernels).  Each returns a hipError_t.
 hipError_t launch_row_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_row_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st);
+hipError_t launch_row_persist_slim(const AttnParams& p, int head_dim, int slots, hipStream_t st);
+hipError_t launch_tile_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st);
 hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_merge_kernel(const AttnParams& p, int head_dim, hipStream_t st);
-hipError_t launch_fused_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_pack(const void* pool, void* staging, const int32_t* dev_ids, int32_t n,
                        size_t block_bytes, hipStream_t st);
 hipError_t launch_unpack(void* pool, const void* staging, const int32_t* dev_ids, int32_t n,

@@ -111,7 +111,7 @@ def test_plan_counts_and_workspace():
     base = p.plan_query(d)
     assert base["decode_rows"] == 2 and base["span_rows"] == int(b.q_len[2:].sum())
     assert base["row_items"] == 2 and base["partial_slots"] == 0 and base["merge_rows"] == 0
-    assert base["tile_items"] == 2            # one 128-row tile per 32-row span, contexts <= 128 keys
+    assert base["tile_items"] == 2            # one tile per 32-row span, contexts <= 128 keys
     assert base["table_entries"] == int(sum(-(-int(c) // 16) for c in b.ctx_len))
     w0 = p.workspace_bytes(d)
     assert w0 > 0 and w0 % 256 == 0
@@ -146,6 +146,6 @@ def test_full_size_plans_are_sane():
         assert info["table_entries"] == int(sum(-(-int(c) // 16) for c in b.ctx_len))
         part = 512 if cfg.head_dim == 256 else 2048
         assert info["row_items"] == int(sum(-(-int(c) // part) for c in b.ctx_len[:cfg.n_decode]))
-        assert info["tile_items"] >= cfg.n_span * (cfg.span_len // 128)
+        assert info["tile_items"] >= cfg.n_span * (cfg.span_len // 256)
         assert 0 < p.workspace_bytes(d) < (4 << 30)
         p.close()
