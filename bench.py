@@ -21,8 +21,10 @@ import numpy as np
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
 # command, scaled by the pack kernel's known 640 000 KiB (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 on this GPU);
-# figures and commands in profiles/fused_persist_kernel_mixed_13b.md.  Only valid for the default workload.
-MEASURED_TRAFFIC_BYTES = {"mixed_13b/fused": (3105728 * 2.0 + 75071) * 1024}
+# figures and commands in profiles/row_and_tile_persist_kernels_mixed_13b.md and
+# profiles/row_persist_kernel_gptj_decode.md.  Only valid for the default launch plan of these workloads.
+MEASURED_TRAFFIC_BYTES = {"mixed_13b/row": (2836516 * 2.0 + 4254) * 1024,
+                          "gptj_decode/row": (660525 * 2.0 + 3277) * 1024}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
 
