@@ -4,8 +4,8 @@
 //
 // One workgroup = one TileItem x one head: up to tile_rows(D) query rows, one wave per 32 rows.
 //   - K and V tiles of 64 keys (4 cache blocks, looked up in the block table) are fetched with
-//     16-byte coalesced loads into registers two tiles ahead, then staged in LDS and shared by
-//     the 4 waves.
+//     16-byte coalesced loads into registers two tiles ahead, then staged in one of two LDS
+//     buffers and shared by all waves; one barrier per tile.
 //   - S^T = K Q^T: A operand = 32 keys x 16 dims from LDS, B operand = this wave's Q^T kept in
 //     registers for the whole item.  In the 32x32 accumulator layout every lane then owns ONE
 //     query column (lane % 32) and 16 of a subtile's 32 keys, so the online softmax needs a
@@ -21,15 +21,8 @@
 
 #include "ic_internal.h"
 
-#ifndef IC_TILE_PIPE
-#define IC_TILE_PIPE 1
-#endif
-
 namespace ic {
 namespace tilep {
-#ifdef IC_TRACE2
-static __device__ long long g_phase[8];
-#endif
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
@@ -66,43 +59,51 @@ struct Staging {
   u32x4 v[TG<D>::kKLoads];
 };
 
-// Global -> registers for one 64-key tile.  ids = the 4 block ids of the tile (wave-uniform).
-// Thread u takes 16-byte chunk u of the K tile and of the V tile: consecutive lanes read
-// consecutive addresses of a (block, head) tile, so every load instruction is fully coalesced.
+// Global -> registers for chunk pair j of one 64-key tile (K chunk and V chunk at the same offset).
+// ids = the 4 block ids of the tile (wave-uniform).  Thread u takes 16-byte chunk u of the K tile
+// and of the V tile: consecutive lanes read consecutive addresses of a (block, head) tile, so every
+// load instruction is fully coalesced.
 template <int D>
-__device__ __forceinline__ void fetch_tile(Staging<D>& st, const char* pool, const int (&ids)[4],
-                                           int head, int H, int tid) {
+__device__ __forceinline__ void fetch_chunk(Staging<D>& st, int j, const char* pool, const int (&ids)[4],
+                                            int head, int H, int tid) {
   using G = TG<D>;
   constexpr int kTileBytes = kBlockSize * D * 2;
   const int64_t blk_stride = (int64_t)2 * H * kTileBytes;
-  const char* kbase = pool + (int64_t)head * kTileBytes;
-  const int64_t v_off = (int64_t)H * kTileBytes;
-#pragma unroll
-  for (int j = 0; j < G::kKLoads; ++j) {
-    const int u = tid + G::kThreads * j;    // 16-byte chunk of the tile
-    const int tok = u / G::kChunks;         // 0..63
-    const int c = u % G::kChunks;
-    // the chunks one wave loads in one instruction never straddle a block: tok / 16 is wave-uniform
-    const int bsel = __builtin_amdgcn_readfirstlane(tok / kBlockSize);
-    const char* a = kbase + (int64_t)ids[bsel] * blk_stride + (tok % kBlockSize) * (D * 2) + c * 16;
-    st.k[j] = *(const u32x4*)a;
-    st.v[j] = *(const u32x4*)(a + v_off);
-  }
+  const int u = tid + G::kThreads * j;    // 16-byte chunk of the tile
+  const int tok = u / G::kChunks;         // 0..63
+  const int c = u % G::kChunks;
+  // the chunks one wave loads in one instruction never straddle a block: tok / 16 is wave-uniform
+  const int bsel = __builtin_amdgcn_readfirstlane(tok / kBlockSize);
+  const char* a = pool + (int64_t)head * kTileBytes + (int64_t)ids[bsel] * blk_stride +
+                  (tok % kBlockSize) * (D * 2) + c * 16;
+  st.k[j] = *(const u32x4*)a;
+  st.v[j] = *(const u32x4*)(a + (int64_t)H * kTileBytes);
 }
 
-// Registers -> LDS, both K and V as [key][dim] rows (padded); with ZERO, V of keys >= n_valid is zeroed.
-template <int D, bool ZERO>
-__device__ __forceinline__ void stage_tile(const Staging<D>& st, uint16_t* ks, uint16_t* vs, int tid,
-                                           int n_valid) {
+template <int D>
+__device__ __forceinline__ void fetch_tile(Staging<D>& st, const char* pool, const int (&ids)[4],
+                                           int head, int H, int tid) {
+#pragma unroll
+  for (int j = 0; j < TG<D>::kKLoads; ++j) fetch_chunk<D>(st, j, pool, ids, head, H, tid);
+}
+
+// Registers -> LDS, K (which = 0) or V (which = 1) of a staged tile, as [key][dim] rows (padded).
+// V of keys >= n_valid is zeroed (dead slots may hold NaN, and 0 * NaN would poison the PV product).
+template <int D>
+__device__ __forceinline__ void stage_half(const Staging<D>& st, int which, uint16_t* ks, uint16_t* vs,
+                                           int tid, int n_valid) {
   using G = TG<D>;
 #pragma unroll
   for (int j = 0; j < G::kKLoads; ++j) {
     const int u = tid + G::kThreads * j;
     const int tok = u / G::kChunks, c = u % G::kChunks;
-    *(u32x4*)(ks + tok * G::kKStride + c * 8) = st.k[j];
-    u32x4 v = st.v[j];
-    if (ZERO && tok >= n_valid) v = (u32x4){0u, 0u, 0u, 0u};
-    *(u32x4*)(vs + tok * G::kVStride + c * 8) = v;
+    if (which == 0) {
+      *(u32x4*)(ks + tok * G::kKStride + c * 8) = st.k[j];
+    } else {
+      u32x4 v = st.v[j];
+      if (tok >= n_valid) v = (u32x4){0u, 0u, 0u, 0u};
+      *(u32x4*)(vs + tok * G::kVStride + c * 8) = v;
+    }
   }
 }
 
@@ -137,7 +138,6 @@ __device__ __forceinline__ void wave_step(const uint16_t* ks, const uint16_t* vs
   for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) s_acc[tt][i] = 0.f;
-#if IC_TILE_PIPE
   // Both 32-key subtiles advance together (two independent accumulators alternate in the MFMA
   // pipe) and the A operands of the next k-step are read from LDS before this step's MFMAs issue.
   {
@@ -157,17 +157,6 @@ __device__ __forceinline__ void wave_step(const uint16_t* ks, const uint16_t* vs
       a1 = n1;
     }
   }
-#else
-#pragma unroll
-  for (int tt = 0; tt < 2; ++tt) {
-    const uint16_t* kp = ks + (32 * tt + col) * G::kKStride + 8 * hl;
-#pragma unroll
-    for (int s = 0; s < G::kQSteps; ++s) {
-      const bf16x8 a = *(const bf16x8*)(kp + 16 * s);
-      s_acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], s_acc[tt], 0, 0, 0);
-    }
-  }
-#endif
   // Scores stay unscaled in the accumulators; the scale (> 0, in log2 units) is folded into the
   // exponent: p = 2^(s*sc - m).
   if (mask) {  // wave-uniform; the empty asm keeps this a branch instead of 32 always-on selects
@@ -207,7 +196,6 @@ __device__ __forceinline__ void wave_step(const uint16_t* ks, const uint16_t* vs
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc_o[dt][i] *= alpha;
   }
-#if IC_TILE_PIPE
   // O^T += V^T P^T, k-step outer so that the kDTiles independent accumulators alternate
   {
     const int lane = col + 32 * hl;
@@ -227,21 +215,17 @@ __device__ __forceinline__ void wave_step(const uint16_t* ks, const uint16_t* vs
       for (int dt = 0; dt < G::kDTiles; ++dt) a[dt] = n[dt];
     }
   }
-#else
-#pragma unroll
-  for (int dt = 0; dt < G::kDTiles; ++dt) {
-#pragma unroll
-    for (int ksp = 0; ksp < 4; ++ksp) {
-      const bf16x8 a = read_vt_operand<D>(vs, 32 * dt, ksp, col + 32 * hl);
-      acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ksp], acc_o[dt], 0, 0, 0);
-    }
-  }
-#endif
+}
+
+// One staged tile: K rows then V rows.
+template <int D>
+constexpr int tile_buf_elems() {
+  return kTileK * TG<D>::kKStride + kTileK * TG<D>::kVStride;
 }
 
 template <int D>
 constexpr int tile_lds_bytes() {
-  return (kTileK * TG<D>::kKStride + kTileK * TG<D>::kVStride) * 2;
+  return 2 * tile_buf_elems<D>() * 2;  // two buffers of bf16
 }
 
 // One TileItem x one head, executed by a workgroup of tile_rows(D) / 32 waves.
@@ -249,8 +233,6 @@ constexpr int tile_lds_bytes() {
 template <int D>
 __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& it, int head, uint16_t* lds) {
   using G = TG<D>;
-  uint16_t* ks = lds;
-  uint16_t* vs = lds + kTileK * G::kKStride;
 
   const int H = p.num_heads;
   const int tid = threadIdx.x;
@@ -292,68 +274,63 @@ __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& i
     for (int i = 0; i < 4; ++i) ids[i] = bt[min(b0 + i, last_blk)];
   };
 
-  // Key tiles are fetched PFD tiles ahead into PFD register sets: one tile of compute (about 2000
-  // cycles) does not cover an HBM round trip under load, two do.  ids_nxt always holds the block
-  // ids of the tile that the next fetch will read, loaded one step before they are needed.
-  constexpr int PFD = D <= 128 ? 2 : 1;  // head_dim 256 has no registers for a second staging set
-#ifdef IC_TRACE2
-  long long ph[6] = {0, 0, 0, 0, 0, 0};
-#define IC_PH(i) { const long long now_ = clock64(); ph[i] += now_ - last_; last_ = now_; }
-#else
-#define IC_PH(i)
-#endif
-  auto step = [&](int t, Staging<D>& st, int (&ids_nxt)[4]) {
-#ifdef IC_TRACE2
-    long long last_ = clock64();
-#endif
-    const int kt = it.k_begin + t * kTileK;
-    if (it.k_end - kt >= kTileK)
-      stage_tile<D, false>(st, ks, vs, tid, kTileK);
-    else
-      stage_tile<D, true>(st, ks, vs, tid, it.k_end - kt);
-    IC_PH(0)
-    __syncthreads();
-    IC_PH(1)
-    if (t + PFD < n_tiles) {
-      fetch_tile<D>(st, pool, ids_nxt, head, H, tid);
-      if (t + PFD + 1 < n_tiles) tile_ids(t + PFD + 1, ids_nxt);
-    }
-    IC_PH(2)
-    if (kt <= wave_pos_hi) {  // otherwise every key of the tile is in this wave's future
-      wave_step<D>(ks, vs, qreg, acc_o, m, l, kt, pos, col, hl, sc, kt + kTileK - 1 > wave_pos_lo);
-    }
-    IC_PH(3)
-    __syncthreads();
-    IC_PH(4)
-  };
-
+  // Pipeline.  LDS holds two tile buffers; registers hold PFD staged tiles (PFD = 2, or 1 for
+  // head_dim 256, which has no registers for a second set).  In step t every wave
+  //   - computes on LDS buffer t % 2,
+  //   - copies tile t+1 from its register set into the other LDS buffer,
+  //   - reloads that register set with tile t+1+PFD,
+  // and ONE barrier ends the step: it publishes tile t+1 and guarantees nobody still reads the
+  // buffer that step t+1 will overwrite.  (Slipping the copies and loads between the MFMAs instead
+  // of issuing them after the tile's arithmetic costs about 45 more registers and was slower.)
+  // ids always holds the block ids of the tile the next fetch will read, loaded a step ahead.
+  constexpr int PFD = D <= 128 ? 2 : 1;
+  constexpr int kBuf = tile_buf_elems<D>();
+  Staging<D> st[PFD];
   int ids[4];
   tile_ids(0, ids);
-  if constexpr (PFD == 2) {
-    Staging<D> st0, st1;
-    fetch_tile<D>(st0, pool, ids, head, H, tid);
-    if (n_tiles > 1) {
-      tile_ids(1, ids);
-      fetch_tile<D>(st1, pool, ids, head, H, tid);
+  fetch_tile<D>(st[0], pool, ids, head, H, tid);
+  if (PFD == 2 && n_tiles > 1) {
+    tile_ids(1, ids);
+    fetch_tile<D>(st[PFD - 1], pool, ids, head, H, tid);
+  }
+  stage_half<D>(st[0], 0, lds, lds + kTileK * G::kKStride, tid, it.k_end - it.k_begin);
+  stage_half<D>(st[0], 1, lds, lds + kTileK * G::kKStride, tid, it.k_end - it.k_begin);
+  if (PFD < n_tiles) {
+    tile_ids(PFD, ids);
+    fetch_tile<D>(st[0], pool, ids, head, H, tid);
+    if (PFD + 1 < n_tiles) tile_ids(PFD + 1, ids);
+  }
+  __syncthreads();
+
+  // step t with its register set fixed at compile time (RS = (t + 1) % PFD holds tile t + 1)
+  auto step = [&](int t, Staging<D>& sreg) {
+    const int kt = it.k_begin + t * kTileK;
+    const uint16_t* ks = lds + (t & 1) * kBuf;
+    const uint16_t* vs = ks + kTileK * G::kKStride;
+    uint16_t* nks = lds + ((t + 1) & 1) * kBuf;
+    uint16_t* nvs = nks + kTileK * G::kKStride;
+    if (kt <= wave_pos_hi)  // otherwise every key of the tile is in this wave's future
+      wave_step<D>(ks, vs, qreg, acc_o, m, l, kt, pos, col, hl, sc, kt + kTileK - 1 > wave_pos_lo);
+    if (t + 1 < n_tiles) {
+      const int n_valid_next = it.k_end - (kt + kTileK);
+      stage_half<D>(sreg, 0, nks, nvs, tid, n_valid_next);
+      stage_half<D>(sreg, 1, nks, nvs, tid, n_valid_next);
     }
-    if (n_tiles > 2) tile_ids(2, ids);
+    if (t + 1 + PFD < n_tiles) {
+      fetch_tile<D>(sreg, pool, ids, head, H, tid);
+      if (t + 2 + PFD < n_tiles) tile_ids(t + 2 + PFD, ids);
+    }
+    __syncthreads();
+  };
+  if constexpr (PFD == 2) {
     for (int t = 0; t < n_tiles; t += 2) {
-      step(t, st0, ids);
-      if (t + 1 < n_tiles) step(t + 1, st1, ids);
+      step(t, st[1]);
+      if (t + 1 < n_tiles) step(t + 1, st[0]);
     }
   } else {
-    Staging<D> st0;
-    fetch_tile<D>(st0, pool, ids, head, H, tid);
-    if (n_tiles > 1) tile_ids(1, ids);
-    for (int t = 0; t < n_tiles; ++t) step(t, st0, ids);
+    for (int t = 0; t < n_tiles; ++t) step(t, st[0]);
   }
 
-#ifdef IC_TRACE2
-  if (lane == 0) {
-    for (int i = 0; i < 5; ++i) atomicAdd((unsigned long long*)&g_phase[i], (unsigned long long)ph[i]);
-    atomicAdd((unsigned long long*)&g_phase[5], (unsigned long long)n_tiles);
-  }
-#endif
   // ---- epilogue: lane holds O^T[d][col] for d = 32 dt + 8 (i/4) + 4 hl + i%4
   l += __shfl_xor(l, 32);
   if (row_ok) {

@@ -20,14 +20,17 @@ def _check_batch(batch, seed, tunings=((0, 0, 0),), tol=TOL):
     want = oracle.attn_batch(batch, pool_bits, q_bits)
     pool, keep = make_pool(pool_bits)
     errs = []
-    for (dp, sp, sk) in tunings:
-        pool.set_tuning(dp, sp, sk)
+    for tn in tunings:
+        if isinstance(tn, dict):
+            pool.set_tuning(**tn)
+        else:
+            pool.set_tuning(*tn)   # (decode_part_tokens, span_part_tokens, span_kernel)
         r = AttnRunner(pool, batch, q_bits)
         out = r.run()
-        assert np.isfinite(W.bf16_bits_to_f64(out)).all(), (dp, sp, sk)
+        assert np.isfinite(W.bf16_bits_to_f64(out)).all(), tn
         e = max_abs_err(out, want)
         errs.append(e)
-        assert e <= tol, (dp, sp, sk, e)
+        assert e <= tol, (tn, e)
         out2 = r.run()
         assert np.array_equal(out, out2), "not deterministic run to run"
     pool.close()
@@ -58,6 +61,51 @@ def test_spans_across_tiles_and_partitions(D, H):
     rng = np.random.default_rng(7 + D)
     batch = W.assemble_batch(H, D, 16, 256, ctx, qlen, rng)
     _check_batch(batch, 77 + D, tunings=((0, 0, 0), (128, 128, 0), (64, 256, 0), (256, 64, 0)))
+
+
+@pytest.mark.parametrize("D,H", [(64, 9), (128, 5), (256, 3)])
+def test_every_launch_path(D, H):
+    """The launch shapes a tuning can select give the same answer as the default: span kernel before
+    the row kernel on one stream, one workgroup per work item, persistent row kernels of both builds
+    with slot counts that do not divide the item count, and the prefetch / load-policy builds."""
+    ctx = [700, 33, 300, 1, 129, 1000, 64, 515, 2100, 90, 17]
+    qlen = [200, 1, 300, 1, 128, 257, 1, 130, 1, 1, 1]
+    rng = np.random.default_rng(31 + D)
+    batch = W.assemble_batch(H, D, 16, 512, ctx, qlen, rng)
+    tunings = [dict(serial_spans=1), dict(serial_spans=1, decode_part_tokens=64, span_part_tokens=128)]
+    tunings += [dict(row_launch=rl, serial_spans=ss, decode_part_tokens=dp)
+                for rl in (1, 2, 3) for ss in (0, 1) for dp in (0, 128)]
+    tunings += [dict(row_launch=2, row_slots=7), dict(row_launch=3, row_slots=13, decode_part_tokens=64),
+                dict(row_slots=1000, decode_part_tokens=64)]
+    tunings += [dict(row_variant=v, row_launch=rl) for v in (1, 2, 3) for rl in (1, 2)]
+    tunings += [dict(span_kernel=1, row_launch=rl, decode_part_tokens=128, span_part_tokens=128) for rl in (1, 2, 3)]
+    _check_batch(batch, 900 + D, tunings=tunings)
+
+
+def test_caller_stream_and_back_to_back_calls():
+    """Calls issued back to back on a caller's (non-default) stream, alternating two batches that share
+    the pool's descriptor ring and side stream, give what each gives alone."""
+    H, D = 5, 128
+    rng = np.random.default_rng(404)
+    b1 = W.assemble_batch(H, D, 16, 512, [700, 33, 300, 1000, 2100], [200, 1, 300, 1, 1], rng)
+    b2 = W.assemble_batch(H, D, 16, 512, [515, 129, 64, 90], [130, 128, 1, 1], rng)
+    pool_bits, q1 = W.make_host_inputs(b1, 1234, poison_unused=False)
+    q2 = W.randn_bf16((b2.total_q_rows, H, D), np.random.default_rng(99))
+    want1 = oracle.attn_batch(b1, pool_bits, q1)
+    want2 = oracle.attn_batch(b2, pool_bits, q2)
+    pool, keep = make_pool(pool_bits)
+    r1, r2 = AttnRunner(pool, b1, q1), AttnRunner(pool, b2, q2)
+    st = torch.cuda.Stream()
+    for r in (r1, r2):
+        r.ws = torch.empty(pool.workspace_bytes(r.desc), dtype=torch.uint8, device=DEV)
+    torch.cuda.synchronize()
+    for _ in range(6):   # more calls in flight than the descriptor ring has slots
+        for r in (r1, r2):
+            pool.paged_attn_mixed(r.desc, r.q.data_ptr(), r.out.data_ptr(), r.ws.data_ptr(), r.ws.numel(), st.cuda_stream)
+    st.synchronize()
+    assert max_abs_err(from_dev_bits(r1.out), want1) <= TOL
+    assert max_abs_err(from_dev_bits(r2.out), want2) <= TOL
+    pool.close()
 
 
 def test_gptj_decode_config_full():
