@@ -213,11 +213,37 @@ def main():
     torch.cuda.synchronize()
     attn_wall_ms = (time.perf_counter() - ta) * 1e3 / args.steps
 
+    # ---- loop 4: the decode sequences alone and the recomputation spans alone (same tables, same q rows)
+    def sub_call_ms(pick):
+        subs = []
+        for b in batches:
+            sel = np.nonzero(pick(b))[0]
+            if len(sel) == 0:
+                return None
+            subs.append(B.HostDesc(b.ctx_len[sel], b.q_len[sel], b.q_start[sel], b.block_tables[sel], b.scale,
+                                   total_q_rows=b.total_q_rows, flags=B.IC_FLAG_TRUSTED))
+            assert pool.workspace_bytes(subs[-1]) <= ws.numel()
+        n = max(10, args.steps // 2)
+        for timed in (False, True):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for i in range(n):
+                k = i & 1
+                pool.paged_attn_mixed(subs[k], qs[k][0].data_ptr(), outs[k].data_ptr(), ws.data_ptr(), ws.numel(), stream)
+            torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / n
+
+    decode_alone_ms = sub_call_ms(lambda b: b.q_len == 1)
+    spans_alone_ms = sub_call_ms(lambda b: b.q_len > 1)
+
     kv_bytes = float(np.mean([b.kv_bytes() for b in batches]))
     dec_bytes = float(np.mean([int(b.ctx_len[b.q_len == 1].astype(np.int64).sum()) * b.token_bytes for b in batches]))
     span_flops = float(np.mean([b.span_flops() for b in batches]))
     swap_moved = 2.0 * scfg.n_move * scfg.block_bytes if do_swap else 0.0   # read + write, per call
     step_bytes = kv_bytes + 2 * swap_moved
+
+    # lower bound of the attention call: all KV bytes at HBM peak, or the spans' flops at MFMA peak
+    roofline_ms = max(kv_bytes / (HBM_PEAK_GBPS * 1e9), span_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)) * 1e3
 
     def avg_ms(k):
         return prof[k]["total_ms"] / prof[k]["launches"] if prof[k]["launches"] else None
@@ -265,6 +291,13 @@ def main():
         "attn": {"kv_bytes": kv_bytes, "ms": round(attn_wall_ms, 4), "sum_kernel_ms": round(attn_ms, 4),
                  "kv_read_GBps": round(kv_bytes / (attn_wall_ms * 1e-3) / 1e9, 1),
                  "frac_hbm_peak": round(kv_bytes / (attn_wall_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                 "decode_kv_bytes": dec_bytes,
+                 "decode_alone_ms": None if decode_alone_ms is None else round(decode_alone_ms, 4),
+                 "decode_alone_GBps": (None if decode_alone_ms is None else
+                                       round(dec_bytes / (decode_alone_ms * 1e-3) / 1e9, 1)),
+                 "spans_alone_ms": None if spans_alone_ms is None else round(spans_alone_ms, 4),
+                 "roofline_time_ms": round(roofline_ms, 4),
+                 "roofline_frac": round(roofline_ms / attn_wall_ms, 4),
                  "span_flops": span_flops,
                  "span_mfma_frac": (round(span_flops / (avg_ms("tile") * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
                                     if prof["tile"]["launches"] else None),

@@ -6,6 +6,8 @@ package; the product path (paper_2402_01869_amd) never does and shares no code w
 paged_attn / paged_attn_items : textbook causal scaled-dot-product attention read through
     block tables (paper Sections 3.1, 4.2 and 4.3), fp64, bf16 bit patterns in.
 pack_blocks / unpack_blocks   : the swap gather / scatter of Section 3.2 as memcpy loops.
+swap_out_layers / swap_in_layers / swap_limit_tokens / swap_schedule : what the layer-by-layer,
+    chunked swap of Section 4.1 leaves behind, its swap limit N_i and the split over iterations.
 Every function is pinned by tests/test_oracle_pins.py; none is "parity unpinned".
 """
 from __future__ import annotations
@@ -39,6 +41,15 @@ def lib():
         _lib.oracle_unpack_blocks.argtypes = [u8p, C.c_int64, C.c_int64, i32p, C.c_int64, u8p]
         _lib.oracle_unpack_blocks.restype = C.c_int
         _lib.oracle_num_threads.restype = C.c_int
+        vpp, i64p = C.POINTER(C.c_void_p), C.POINTER(C.c_int64)
+        _lib.oracle_swap_out_layers.argtypes = [vpp, C.c_int64, C.c_int64, C.c_int64, i32p, C.c_int64, u8p, C.c_int64]
+        _lib.oracle_swap_out_layers.restype = C.c_int
+        _lib.oracle_swap_in_layers.argtypes = [vpp, C.c_int64, C.c_int64, C.c_int64, i32p, C.c_int64, u8p, C.c_int64]
+        _lib.oracle_swap_in_layers.restype = C.c_int
+        _lib.oracle_swap_limit_tokens.argtypes = [C.c_double, C.c_double, C.c_double]
+        _lib.oracle_swap_limit_tokens.restype = C.c_int64
+        _lib.oracle_swap_schedule.argtypes = [C.c_int64, C.c_int64, i64p, C.c_int64, i64p]
+        _lib.oracle_swap_schedule.restype = C.c_int64
     return _lib
 
 
@@ -141,3 +152,45 @@ def unpack_blocks(pool_bytes: np.ndarray, ids, staging: np.ndarray) -> None:
 
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
+
+
+def _layer_ptrs(pools):
+    for a in pools:
+        assert a.dtype == np.uint8 and a.flags.c_contiguous and a.shape == pools[0].shape
+    return (C.c_void_p * len(pools))(*[a.ctypes.data for a in pools])
+
+
+def swap_out_layers(pools, ids, layer_stride: Optional[int] = None) -> np.ndarray:
+    """host[l][i] = pools[l][ids[i]] for every layer l; pools: list of uint8 [blocks][block_bytes].
+
+    Returns uint8 [L][layer_stride]; bytes past n * block_bytes of a layer are left 0xEE."""
+    ids = _c(ids, np.int32)
+    nblk, bb = pools[0].shape
+    stride = ids.shape[0] * bb if layer_stride is None else int(layer_stride)
+    host = np.full((len(pools), stride), 0xEE, dtype=np.uint8)
+    _check(lib().oracle_swap_out_layers(_layer_ptrs(pools), len(pools), nblk, bb, _p(ids, C.c_int32),
+                                        ids.shape[0], _p(host, C.c_uint8), stride))
+    return host
+
+
+def swap_in_layers(pools, ids, host: np.ndarray) -> None:
+    """pools[l][ids[i]] = host[l][i], in place; host uint8 [L][layer_stride]; ids distinct."""
+    ids = _c(ids, np.int32)
+    nblk, bb = pools[0].shape
+    assert host.dtype == np.uint8 and host.flags.c_contiguous and host.shape[0] == len(pools)
+    _check(lib().oracle_swap_in_layers(_layer_ptrs(pools), len(pools), nblk, bb, _p(ids, C.c_int32),
+                                       ids.shape[0], _p(host, C.c_uint8), host.shape[1]))
+
+
+def swap_limit_tokens(t_fwd: float, bandwidth: float, token_bytes: float) -> int:
+    """Swap limit N_i: tokens whose movement at `bandwidth` bytes/s takes t_fwd seconds, rounded down."""
+    return int(lib().oracle_swap_limit_tokens(float(t_fwd), float(bandwidth), float(token_bytes)))
+
+
+def swap_schedule(total_blocks: int, block_size: int, limits) -> tuple:
+    """Blocks moved per iteration under per-iteration token limits -> (iterations used, int64 array)."""
+    limits = _c(limits, np.int64)
+    out = np.zeros(limits.shape[0], dtype=np.int64)
+    used = int(lib().oracle_swap_schedule(int(total_blocks), int(block_size), _p(limits, C.c_int64),
+                                          limits.shape[0], _p(out, C.c_int64)))
+    return used, out

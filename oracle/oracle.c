@@ -19,6 +19,11 @@
  *    reproduces what a one-shot causal prefill would have produced.
  *  - Swap of scattered blocks (Section 3.2, swap-based approach): gather the
  *    listed blocks into a contiguous staging buffer, and scatter them back.
+ *  - Swap pipelining and chunking (Section 4.1): what a layer-by-layer swap of
+ *    the listed blocks leaves in host memory / in the pools (the pipeline only
+ *    changes WHEN bytes move, so the result is the per-layer gather / scatter),
+ *    the swap limit N_i that solves T_swap(N_i) = T_fwd(B_i), and the split of
+ *    one sequence's swap over iterations under those limits.
  *
  * The attention formula itself is not printed in the paper (it inherits the
  * serving stack's kernels, Section 4.5); it is the standard scaled dot-product
@@ -191,6 +196,75 @@ int oracle_unpack_blocks(uint8_t *pool, int64_t num_blocks, int64_t block_bytes,
     for (int64_t i = 0; i < n; ++i)
         memcpy(pool + (int64_t)ids[i] * block_bytes, staging + i * block_bytes, (size_t)block_bytes);
     return 0;
+}
+
+/*
+ * Section 4.1, swap pipelining: each layer's swapping is one stage.  Whatever the overlap, once
+ * all stages are through, layer l's listed blocks sit in list order at host + l * layer_stride.
+ */
+int oracle_swap_out_layers(const uint8_t *const *pools, int64_t num_layers, int64_t num_blocks,
+                           int64_t block_bytes, const int32_t *ids, int64_t n, uint8_t *host,
+                           int64_t layer_stride)
+{
+    if (layer_stride < n * block_bytes) return -2;
+    for (int64_t l = 0; l < num_layers; ++l) {
+        int rc = oracle_pack_blocks(pools[l], num_blocks, block_bytes, ids, n, host + l * layer_stride);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+/* The way back: layer l's pool receives host + l * layer_stride at the listed (distinct) blocks. */
+int oracle_swap_in_layers(uint8_t *const *pools, int64_t num_layers, int64_t num_blocks,
+                          int64_t block_bytes, const int32_t *ids, int64_t n, const uint8_t *host,
+                          int64_t layer_stride)
+{
+    if (layer_stride < n * block_bytes) return -2;
+    for (int64_t l = 0; l < num_layers; ++l) {
+        int rc = oracle_unpack_blocks(pools[l], num_blocks, block_bytes, ids, n, host + l * layer_stride);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+/*
+ * Section 4.1, swap chunking.  T_swap(N) = N * M / bandwidth (the paper computes T_swap from the
+ * swapping bandwidth and the per-token memory M); the swap limit of an iteration whose forward
+ * pass takes t_fwd is the N with T_swap(N) = t_fwd, i.e. the number of tokens whose movement
+ * hides behind the forward pass.  Tokens are whole, so the limit is rounded down.
+ * Returns -1 for arguments outside the model (negative time, non-positive bandwidth or M).
+ */
+int64_t oracle_swap_limit_tokens(double t_fwd, double bandwidth, double token_bytes)
+{
+    if (!(t_fwd >= 0.0) || !(bandwidth > 0.0) || !(token_bytes > 0.0)) return -1;
+    double n = floor(t_fwd * bandwidth / token_bytes);
+    if (n > 9.0e18) return INT64_MAX;
+    return (int64_t)n;
+}
+
+/*
+ * Section 4.1: the swap of one sequence is split over iterations so that iteration i moves at
+ * most its swap limit limits[i] (tokens).  The cache moves in whole blocks of block_size tokens,
+ * so an iteration moves floor(limit / block_size) blocks at most (reading: a partial block cannot
+ * be moved, and rounding up would exceed what the forward pass hides).  out_blocks[i] receives
+ * the blocks moved in iteration i; returns the number of iterations used (n_iters + 1 if the
+ * limits given do not suffice), or -1 for bad arguments.
+ */
+int64_t oracle_swap_schedule(int64_t total_blocks, int64_t block_size, const int64_t *limits,
+                             int64_t n_iters, int64_t *out_blocks)
+{
+    if (total_blocks < 0 || block_size < 1 || n_iters < 0) return -1;
+    int64_t left = total_blocks, used = 0;
+    for (int64_t i = 0; i < n_iters; ++i) {
+        if (limits[i] < 0) return -1;
+        int64_t can = limits[i] / block_size;
+        int64_t mv = left < can ? left : can;
+        out_blocks[i] = mv;
+        left -= mv;
+        if (mv > 0) used = i + 1;
+        if (left == 0) { for (int64_t j = i + 1; j < n_iters; ++j) out_blocks[j] = 0; break; }
+    }
+    return left > 0 ? n_iters + 1 : used;
 }
 
 int oracle_num_threads(void)

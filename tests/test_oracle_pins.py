@@ -316,3 +316,100 @@ def test_pack_order_duplicates_and_errors():
         oracle.unpack_blocks(pool.copy(), [2, 2], st[:2])   # duplicate destinations
     with pytest.raises(oracle.OracleError):
         oracle.unpack_blocks(pool.copy(), [-1], st[:1])
+
+
+# ---------------------------------------------------------------------------------------------
+# Section 4.1: layer-pipelined, chunked swap
+# ---------------------------------------------------------------------------------------------
+def _layer_pools(L, nb, bb, seed):
+    rng = np.random.default_rng(seed)
+    return [rng.integers(0, 256, size=(nb, bb), dtype=np.uint8) for _ in range(L)]
+
+
+def test_swap_out_layers_equals_numpy_gather_per_layer():
+    # Catches: a layer written to another layer's slice, list order lost, stride ignored.
+    L, nb, bb = 5, 23, 48
+    pools = _layer_pools(L, nb, bb, 3)
+    ids = np.array([7, 0, 22, 7, 3], dtype=np.int32)       # duplicate sources are legal on the way out
+    stride = len(ids) * bb + 32                            # padded layer stride
+    host = oracle.swap_out_layers(pools, ids, stride)
+    assert host.shape == (L, stride)
+    for l in range(L):
+        assert np.array_equal(host[l, :len(ids) * bb].reshape(len(ids), bb), pools[l][ids])
+        assert (host[l, len(ids) * bb:] == 0xEE).all()     # padding untouched
+
+
+def test_swap_in_layers_inverts_swap_out_and_touches_nothing_else():
+    # out to host, wipe the pools, in to OTHER blocks: the listed blocks reappear, all others keep
+    # their bytes.  Catches: scatter through the wrong list, a layer skipped, writes off the list.
+    L, nb, bb = 4, 40, 64
+    pools = _layer_pools(L, nb, bb, 4)
+    orig = [p.copy() for p in pools]
+    rng = np.random.default_rng(5)
+    perm = rng.permutation(nb).astype(np.int32)
+    src, dst = perm[:9], perm[9:18]
+    host = oracle.swap_out_layers(pools, src)
+    oracle.swap_in_layers(pools, dst, host)
+    for l in range(L):
+        assert np.array_equal(pools[l][dst], orig[l][src])
+        others = np.setdiff1d(np.arange(nb), dst)
+        assert np.array_equal(pools[l][others], orig[l][others])
+    # back to the same ids: identity on every pool
+    pools2 = [p.copy() for p in orig]
+    oracle.swap_in_layers(pools2, src, oracle.swap_out_layers(pools2, src))
+    assert all(np.array_equal(a, b) for a, b in zip(pools2, orig))
+
+
+def test_swap_layers_reject_bad_lists():
+    pools = _layer_pools(2, 8, 16, 6)
+    with pytest.raises(oracle.OracleError):
+        oracle.swap_out_layers(pools, [1, 8])
+    host = oracle.swap_out_layers(pools, [1, 2])
+    with pytest.raises(oracle.OracleError):
+        oracle.swap_in_layers(pools, [3, 3], host)         # duplicate destinations
+    with pytest.raises(oracle.OracleError):
+        oracle.swap_out_layers(pools, [1, 2], layer_stride=16)   # stride shorter than the payload
+
+
+def test_swap_limit_solves_t_swap_equals_t_fwd():
+    # Worked by hand: 13B-shaped M = 40 layers x 20 KiB = 819 200 B per token; a 30 ms forward pass
+    # over a 32 GB/s link hides 0.03 * 32e9 / 819200 = 1171.875 -> 1171 tokens.
+    assert oracle.swap_limit_tokens(0.030, 32e9, 819200) == 1171
+    # exact cases (powers of two keep fp64 exact): T_swap(N) = N * M / BW = T_fwd has the root N
+    assert oracle.swap_limit_tokens(0.5, 2.0 ** 30, 2.0 ** 20) == 512
+    assert oracle.swap_limit_tokens(0.0, 1e9, 1024) == 0
+    # defining property on random inputs: N moves in time, N + 1 does not.  Catches an inverted
+    # ratio (M / BW), a rounding up, and a bits/bytes factor.
+    rng = np.random.default_rng(7)
+    for _ in range(200):
+        t = float(rng.uniform(1e-3, 0.2)); bw = float(rng.uniform(1e9, 128e9)); m = float(rng.integers(1024, 4 << 20))
+        n = oracle.swap_limit_tokens(t, bw, m)
+        assert n * m / bw <= t * (1 + 1e-12) and (n + 1) * m / bw > t * (1 - 1e-12)
+    # doubling the link or the time doubles the limit (up to the rounding), doubling M halves it
+    assert oracle.swap_limit_tokens(0.04, 64e9, 1 << 20) in (2 * oracle.swap_limit_tokens(0.04, 32e9, 1 << 20),
+                                                             2 * oracle.swap_limit_tokens(0.04, 32e9, 1 << 20) + 1)
+    assert oracle.swap_limit_tokens(-1.0, 1e9, 1024) == -1 and oracle.swap_limit_tokens(1.0, 0.0, 1024) == -1
+
+
+def test_swap_schedule_respects_limits_and_moves_everything_once():
+    # brute force in plain Python next to the oracle; catches: rounding blocks up past the limit,
+    # moving more than is left, dropping the remainder.
+    rng = np.random.default_rng(8)
+    for _ in range(100):
+        total = int(rng.integers(0, 200)); bs = int(rng.choice([1, 8, 16]))
+        limits = rng.integers(0, 40 * bs, size=int(rng.integers(1, 30))).astype(np.int64)
+        used, blocks = oracle.swap_schedule(total, bs, limits)
+        assert (blocks * bs <= limits).all() and (blocks >= 0).all()
+        left, want, want_used = total, [], 0
+        for i, lim in enumerate(limits):
+            mv = min(left, int(lim) // bs); want.append(mv); left -= mv
+            if mv:
+                want_used = i + 1
+        assert list(blocks) == want
+        if left:
+            assert used == len(limits) + 1 and blocks.sum() == total - left
+        else:
+            assert used == want_used and blocks.sum() == total
+    # hand example: 10 blocks of 16 tokens under limits 40, 16, 15, 100, 100 tokens -> 2, 1, 0, 6, 1
+    used, blocks = oracle.swap_schedule(10, 16, [40, 16, 15, 100, 100])
+    assert used == 5 and list(blocks) == [2, 1, 0, 6, 1]
