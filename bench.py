@@ -41,6 +41,12 @@ def parse_args():
     ap.add_argument("--serial-spans", type=int, default=0)
     ap.add_argument("--row-launch", type=int, default=0)
     ap.add_argument("--row-slots", type=int, default=0)
+    ap.add_argument("--mode", default="hot_path", choices=["hot_path", "swap_pipeline"],
+                    help="hot_path: the step described above (default); swap_pipeline: the layer-pipelined "
+                         "swap to pinned host memory, alone and behind the attention call")
+    ap.add_argument("--layers", type=int, default=8, help="swap_pipeline: layers (pools) moved per call")
+    ap.add_argument("--swap-blocks", type=int, default=512, help="swap_pipeline: blocks per layer per call")
+    ap.add_argument("--stages", type=int, default=2, help="swap_pipeline: staging buffers")
     ap.add_argument("--no-swap", action="store_true", help="time the attention call only")
     ap.add_argument("--decode-only", action="store_true", help="drop the recomputation spans from the batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -98,12 +104,160 @@ def cpu_baseline(batch, pool_t, q_bits, target_s):
                       f"({used} visible keys x {batch.token_bytes} B of KV per key, counted once per row)"}
 
 
+def swap_pipeline_bench(args):
+    """Section 4.1 on this machine: L layers' blocks gathered, moved over the host link and scattered
+    back, layer by layer; first alone, then while the 13B-shaped attention call runs in a loop."""
+    import torch
+    from paper_2402_01869_amd import binding as B
+    from paper_2402_01869_amd import workloads as W
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    acfg, scfg = W.MIXED_13B, W.KV_SWAP
+    H, D, L, n = acfg.num_heads, acfg.head_dim, args.layers, args.swap_blocks
+    bb = scfg.block_bytes
+    lay_blocks = max(4 * n, 2048)
+    rng = np.random.default_rng(scfg.seed)
+    lay_t = []
+    for l in range(L):
+        t = torch.empty((lay_blocks, bb), dtype=torch.uint8, device=dev)
+        W.fill_bytes_device(t, scfg.seed + l)
+        lay_t.append(t)
+    lay = [B.KvPool(B.make_cfg(lay_blocks, H, D), t.data_ptr(), t.numel()) for t in lay_t]
+    need = B.LayerSwapper.staging_bytes(lay[0], L, n, args.stages)
+    staging = torch.empty(need, dtype=torch.uint8, device=dev)
+    sw = B.LayerSwapper(lay, n, staging.data_ptr(), need, args.stages)
+    perm = rng.permutation(lay_blocks).astype(np.int32)
+    src, dst = perm[:n], perm[n:2 * n]
+    pin = B.PinnedBuffer(L * n * bb)
+    moved = float(L) * n * bb
+    reps = max(3, min(args.steps, 10))
+
+    def timed(fn):
+        fn(); sw.sync()
+        ts = []
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn(); sw.sync()
+            ts.append(time.perf_counter() - t0)
+        return float(np.median(ts)), float(np.min(ts))
+
+    out_med, out_min = timed(lambda: sw.swap_out(src, pin.ptr, n * bb))
+    in_med, in_min = timed(lambda: sw.swap_in(dst, pin.ptr, n * bb))
+
+    # link ceiling: one contiguous copy of the same size, device <-> the same pinned memory
+    flat = torch.empty(int(moved), dtype=torch.uint8, device=dev)
+    pin_t = torch.from_numpy(pin.array)
+
+    def copy_time(d2h):
+        ts = []
+        for _ in range(reps + 1):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            if d2h:
+                pin_t.copy_(flat, non_blocking=True)
+            else:
+                flat.copy_(pin_t, non_blocking=True)
+            torch.cuda.synchronize()
+            ts.append(time.perf_counter() - t0)
+        return float(np.median(ts[1:]))
+    d2h_s, h2d_s = copy_time(True), copy_time(False)
+
+    # attention loop alone, then with swaps queued behind it
+    pool_t = torch.empty(W.pool_shape(acfg.pool_blocks, H, 16, D), dtype=torch.bfloat16, device=dev)
+    W.fill_pool_device_normal(pool_t, acfg.seed)
+    pool = B.KvPool.from_tensor(pool_t, H, D)
+    batch = W.make_batch(acfg, acfg.seed)
+    desc = B.HostDesc.from_batch(batch, flags=0)
+    q = torch.from_numpy(W.randn_bf16((batch.total_q_rows, H, D), np.random.default_rng(1)).view(np.int16)).to(dev)
+    out = torch.zeros_like(q)
+    ws = torch.empty(pool.workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    pool.paged_attn_mixed(desc, q.data_ptr(), out.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+    desc.struct.flags = B.IC_FLAG_TRUSTED
+
+    cur = torch.cuda.current_stream()
+
+    def attn_loop(k, period, swap_fn=None):
+        """k attention calls on the caller's stream; with period > 0 a swap-out of all layers is handed to
+        the swapper before every period-th call (one chunk per iteration, as the scheduler would), so the
+        link is busy for the whole loop -> (ms per attention call, swaps queued, seconds until they are
+        through, average kernel times from a second pass with an event pair around every kernel)."""
+        def one_pass():
+            n_sw = 0
+            for i in range(k):
+                if period and i % period == 0:
+                    swap_fn()
+                    n_sw += 1
+                pool.paged_attn_mixed(desc, q.data_ptr(), out.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+            cur.synchronize()                  # the caller's stream only: the swapper has its own
+            return n_sw
+        for i in range(args.warmup):
+            pool.paged_attn_mixed(desc, q.data_ptr(), out.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n_sw = one_pass()
+        t1 = time.perf_counter()
+        sw.sync()
+        t2 = time.perf_counter()
+        pool.prof_begin(5 * k + 8)
+        one_pass()
+        pr = pool.prof_end()
+        sw.sync()
+        kern = {a: round(pr[a]["total_ms"] / pr[a]["launches"], 4) for a in ("upload", "row", "tile", "merge") if pr[a]["launches"]}
+        return (t1 - t0) * 1e3 / k, n_sw, t2 - t0, kern
+
+    k = max(args.steps, 100)
+    alone_ms, _, _, alone_kern = attn_loop(k, 0)
+    period = max(1, int(out_med * 1e3 / alone_ms))       # attention calls that fit in one swap
+    behind_ms, n_swaps, swap_s, behind_kern = attn_loop(k, period, lambda: sw.swap_out(src, pin.ptr, n * bb))
+    in_ms, n_in, in_s, in_kern = attn_loop(k, period, lambda: sw.swap_in(dst, pin.ptr, n * bb))
+    link = moved / out_med
+    token_bytes = acfg.token_bytes          # one layer's M; t_fwd below is one layer's attention call
+    result = {
+        "metric": "layer-pipelined KV swap over the host link, GB/s", "value": round(moved / out_med / 1e9, 2),
+        "unit": "GB/s", "n_gpus": 1, "steps": reps, "warmup": 1, "ms_per_step": round(out_med * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"swap pipeline: {L} layers x {n} blocks x {bb // 1024} KiB (13B-shaped layer), "
+                               f"{args.stages} staging buffers, pools of {lay_blocks} blocks"},
+        "swap_out": {"bytes": moved, "median_ms": round(out_med * 1e3, 3), "min_ms": round(out_min * 1e3, 3),
+                     "GBps": round(moved / out_med / 1e9, 2),
+                     "frac_of_contiguous_copy": round(d2h_s / out_med, 4)},
+        "swap_in": {"bytes": moved, "median_ms": round(in_med * 1e3, 3), "min_ms": round(in_min * 1e3, 3),
+                    "GBps": round(moved / in_med / 1e9, 2),
+                    "frac_of_contiguous_copy": round(h2d_s / in_med, 4)},
+        "contiguous_copy": {"d2h_GBps": round(moved / d2h_s / 1e9, 2), "h2d_GBps": round(moved / h2d_s / 1e9, 2)},
+        "behind_attention": {"attn_calls": k, "attn_ms_alone": round(alone_ms, 4),
+                             "attn_ms_with_swap_out_running": round(behind_ms, 4),
+                             "attn_slowdown": round(behind_ms / alone_ms - 1.0, 4),
+                             "kernel_ms_alone": alone_kern, "kernel_ms_with_swap_out_running": behind_kern,
+                             "swap_outs_queued": n_swaps, "attn_calls_per_swap_out": period,
+                             "swap_out_GBps_meanwhile": round(n_swaps * moved / swap_s / 1e9, 2),
+                             "attn_ms_with_swap_in_running": round(in_ms, 4),
+                             "attn_slowdown_swap_in": round(in_ms / alone_ms - 1.0, 4),
+                             "kernel_ms_with_swap_in_running": in_kern,
+                             "swap_in_GBps_meanwhile": round(n_in * moved / in_s / 1e9, 2)},
+        "swap_limit": {"t_fwd_s": round(alone_ms * 1e-3, 6), "link_bytes_per_s": round(link, 0),
+                       "token_bytes": token_bytes,
+                       "tokens_per_iteration": B.swap_limit_tokens(alone_ms * 1e-3, link, token_bytes),
+                       "note": "t_fwd is one layer's attention call and token_bytes one layer's M: the ratio "
+                               "equals the whole model's if every layer behaves alike"},
+    }
+    print(json.dumps(result))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this hot path runs on ONE GPU (no sharding or collectives are built); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.mode == "swap_pipeline":
+        sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+        from paper_2402_01869_amd import binding as B
+        B.lib()
+        return swap_pipeline_bench(args)
     import torch
     sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
     from paper_2402_01869_amd import binding as B
@@ -251,7 +405,7 @@ def main():
     plan = pool.plan_query(descs[0])
     attn_ms = sum((avg_ms(k) or 0.0) * (prof[k]["launches"] / args.steps) for k in ("row", "tile", "merge"))
     kernels = {}
-    for k in ("row", "tile", "merge", "pack", "unpack"):
+    for k in ("upload", "row", "tile", "merge", "pack", "unpack"):
         if prof[k]["launches"]:
             kernels[k] = {"launches": prof[k]["launches"], "avg_ms": round(avg_ms(k), 5),
                           "min_ms": round(prof[k]["min_ms"], 5), "max_ms": round(prof[k]["max_ms"], 5)}

@@ -170,11 +170,86 @@ int kv_unpack_blocks(ic_pool* pool, const int32_t* host_ids, int32_t n, const vo
 int ic_check_ids(const ic_pool_cfg* cfg, const int32_t* host_ids, int32_t n, int require_distinct);
 
 /* ------------------------------------------------------------------------------------------
+ * Layer-pipelined, chunked swap between the paged pools of a model's layers and pinned host memory
+ * (Section 4.1).  Swap pipelining: one layer's swapping is one pipeline stage; the stages run on the
+ * swapper's own streams, behind the caller's forward pass, which waits only for the layer it needs.
+ * Swap chunking: one call moves only as many blocks as the iteration's swap limit allows
+ * (ic_swap_limit_tokens), the rest of the sequence follows in later iterations (ic_swap_schedule).
+ *
+ * A swapper serves L pools of ONE shape (the L layers of a model; a multi-layer cache is L pools).
+ * It owns two streams of default priority, one per direction (swap-out and swap-in run beside each
+ * other), and cycles `num_stages` staging buffers, each max_blocks * kv_block_bytes() bytes, carved from the
+ * caller's dev_staging.  Per layer l and list position i, with blk = kv_block_bytes():
+ *   kv_swap_out_layers:  host[l * layer_stride + i * blk ..+blk) <- pool_l[host_ids[i]]
+ *   kv_swap_in_layers:   pool_l[host_ids[i]] <- host[l * layer_stride + i * blk ..+blk)   (ids distinct)
+ * `host` is pinned host memory (ic_host_alloc, or any hipHostMalloc'ed block; pageable memory is
+ * refused with IC_EUNSUPPORTED: copies from it would not be asynchronous) and must stay valid and
+ * unmodified until the layers are through.  Both calls return at once.  Work already queued on
+ * `after_stream` (NULL = default stream) when the call is made finishes before the first byte moves:
+ * pass the stream that wrote (swap-out) or last read (swap-in) the listed blocks.
+ * Order later work with ic_swapper_wait_layer (a stream waits until layer l of the latest call in
+ * that direction is through: for swap-in the layer's blocks are then readable, for swap-out they
+ * may be reused), ic_swapper_sync_layer or ic_swapper_sync (the host waits).
+ * One host thread drives a swapper.  Byte-exact.  n = 0 succeeds and does nothing.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct ic_swapper ic_swapper;
+
+typedef struct {
+  int32_t num_layers; /* L >= 1                                                        */
+  int32_t max_blocks; /* most blocks one call may move per layer, >= 1                 */
+  int32_t num_stages; /* staging buffers cycled layer by layer, 2..8                   */
+  int32_t reserved;   /* must be 0                                                     */
+} ic_swapper_cfg;
+
+enum { IC_SWAP_OUT = 0, IC_SWAP_IN = 1 };
+
+/* num_stages * max_blocks * kv_block_bytes(pool0); 0 on a NULL or invalid argument. */
+size_t ic_swapper_staging_bytes(const ic_swapper_cfg* cfg, const ic_pool* pool0);
+
+/* layer_pools: host array of L pools with identical ic_pool_cfg (IC_EINVAL otherwise); they must
+ * outlive the swapper.  dev_staging: device, 16-byte aligned, >= ic_swapper_staging_bytes(), not
+ * overlapping any pool.  Touches no GPU state: streams and events are created by the first swap. */
+int ic_swapper_create(const ic_swapper_cfg* cfg, ic_pool* const* layer_pools, void* dev_staging,
+                      size_t staging_bytes, ic_swapper** out);
+int ic_swapper_destroy(ic_swapper* sw); /* waits for queued swaps, frees library-owned buffers */
+
+int kv_swap_out_layers(ic_swapper* sw, const int32_t* host_ids, int32_t n, void* pinned_host_dst,
+                       size_t layer_stride_bytes, void* after_stream);
+int kv_swap_in_layers(ic_swapper* sw, const int32_t* host_ids, int32_t n, const void* pinned_host_src,
+                      size_t layer_stride_bytes, void* after_stream);
+
+int ic_swapper_wait_layer(ic_swapper* sw, int32_t direction, int32_t layer, void* hip_stream);
+int ic_swapper_sync_layer(ic_swapper* sw, int32_t direction, int32_t layer);
+int ic_swapper_sync(ic_swapper* sw);
+
+/* Pinned host memory for swap targets (hipHostMalloc / hipHostFree).  NULL on failure. */
+void* ic_host_alloc(size_t bytes);
+int ic_host_free(void* p);
+
+/*
+ * Swap limit N_i of Section 4.1: with T_swap(N) = N * token_bytes / link_bytes_per_s, the number of
+ * tokens whose swap takes as long as the iteration's forward pass, T_swap(N_i) = t_fwd_s, rounded
+ * down to whole tokens (computed as floor(t_fwd_s * link_bytes_per_s / token_bytes) in fp64).
+ * token_bytes is M summed over the layers that move.  Returns -1 on arguments outside the model.
+ */
+int64_t ic_swap_limit_tokens(double t_fwd_s, double link_bytes_per_s, double token_bytes);
+
+/*
+ * Split the swap of total_blocks blocks over iterations whose limits (tokens) are limits[0..n):
+ * iteration i moves min(blocks left, limits[i] / block_size) whole blocks into out_blocks[i].
+ * Returns the iterations used, n_iters + 1 if the limits do not cover the whole swap, -1 on bad
+ * arguments.  Host only.
+ */
+int64_t ic_swap_schedule(int64_t total_blocks, int32_t block_size, const int64_t* limits,
+                         int64_t n_iters, int64_t* out_blocks);
+
+/* ------------------------------------------------------------------------------------------
  * Per-kernel timing with HIP events on the launch stream (for roofline reports).  Between
  * ic_prof_begin and ic_prof_end every kernel the pool launches is bracketed by an event pair.
  * ic_prof_end synchronises the recorded events and returns totals per kernel kind.
  * ------------------------------------------------------------------------------------------ */
-enum { IC_K_ROW = 0, IC_K_TILE = 1, IC_K_MERGE = 2, IC_K_PACK = 3, IC_K_UNPACK = 4, IC_K_COUNT = 5 };
+enum { IC_K_ROW = 0, IC_K_TILE = 1, IC_K_MERGE = 2, IC_K_PACK = 3, IC_K_UNPACK = 4, IC_K_UPLOAD = 5, IC_K_COUNT = 6 };
+/* IC_K_UPLOAD: the kernel that copies a call's descriptor from pinned host memory to the device. */
 typedef struct {
   int32_t launches[IC_K_COUNT];
   float total_ms[IC_K_COUNT];

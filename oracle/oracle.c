@@ -254,9 +254,10 @@ int64_t oracle_swap_schedule(int64_t total_blocks, int64_t block_size, const int
                              int64_t n_iters, int64_t *out_blocks)
 {
     if (total_blocks < 0 || block_size < 1 || n_iters < 0) return -1;
+    for (int64_t i = 0; i < n_iters; ++i)
+        if (limits[i] < 0) return -1;
     int64_t left = total_blocks, used = 0;
     for (int64_t i = 0; i < n_iters; ++i) {
-        if (limits[i] < 0) return -1;
         int64_t can = limits[i] / block_size;
         int64_t mv = left < can ? left : can;
         out_blocks[i] = mv;

@@ -19,15 +19,19 @@ IC_OK = 0
 IC_ENULL, IC_EINVAL, IC_ERANGE, IC_ESIZE, IC_EALIGN = -1, -2, -3, -4, -5
 IC_EDUP, IC_EUNSUPPORTED, IC_EOVERLAP, IC_EHIP, IC_ENOMEM = -6, -7, -8, -9, -10
 IC_FLAG_TRUSTED = 1
-IC_K_ROW, IC_K_TILE, IC_K_MERGE, IC_K_PACK, IC_K_UNPACK, IC_K_COUNT = 0, 1, 2, 3, 4, 5
-KERNEL_NAMES = ("row", "tile", "merge", "pack", "unpack")
+IC_K_ROW, IC_K_TILE, IC_K_MERGE, IC_K_PACK, IC_K_UNPACK, IC_K_UPLOAD, IC_K_COUNT = 0, 1, 2, 3, 4, 5, 6
+KERNEL_NAMES = ("row", "tile", "merge", "pack", "unpack", "upload")
 
 EXPORTS = (
     "ic_strerror", "kv_pool_init", "kv_pool_destroy", "kv_block_bytes",
     "paged_attn_mixed_workspace_bytes", "paged_attn_mixed", "ic_check_batch", "ic_pool_set_tuning",
     "ic_plan_query", "kv_pack_blocks", "kv_unpack_blocks", "ic_check_ids", "ic_prof_begin",
     "ic_prof_end",
+    "ic_swapper_staging_bytes", "ic_swapper_create", "ic_swapper_destroy", "kv_swap_out_layers",
+    "kv_swap_in_layers", "ic_swapper_wait_layer", "ic_swapper_sync_layer", "ic_swapper_sync",
+    "ic_host_alloc", "ic_host_free", "ic_swap_limit_tokens", "ic_swap_schedule",
 )
+IC_SWAP_OUT, IC_SWAP_IN = 0, 1
 
 
 class PoolCfg(C.Structure):
@@ -63,6 +67,10 @@ class ProfStats(C.Structure):
                 ("min_ms", C.c_float * IC_K_COUNT), ("max_ms", C.c_float * IC_K_COUNT)]
 
 
+class SwapperCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("num_layers", "max_blocks", "num_stages", "reserved")]
+
+
 class InferceptError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -79,6 +87,14 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2402_01869_amd.build` "
                               "(there is no CPU fallback)")
+        # The library must share ONE HIP runtime with the process that owns the device memory it is
+        # handed.  PyTorch ships its own copy of the runtime under the same SONAME: loaded first, it
+        # is the one this library binds to; loaded second, the process would hold two runtimes that
+        # do not know each other's allocations.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
         L.ic_strerror.argtypes, L.ic_strerror.restype = [C.c_int], C.c_char_p
@@ -96,8 +112,26 @@ def lib():
         L.ic_check_ids.argtypes = [C.POINTER(PoolCfg), i32p, C.c_int32, C.c_int]
         L.ic_prof_begin.argtypes = [vp, C.c_int32]
         L.ic_prof_end.argtypes = [vp, C.POINTER(ProfStats)]
+        i64p = C.POINTER(C.c_int64)
+        L.ic_swapper_staging_bytes.argtypes = [C.POINTER(SwapperCfg), vp]
+        L.ic_swapper_staging_bytes.restype = C.c_size_t
+        L.ic_swapper_create.argtypes = [C.POINTER(SwapperCfg), C.POINTER(vp), vp, C.c_size_t, C.POINTER(vp)]
+        L.ic_swapper_destroy.argtypes = [vp]
+        L.kv_swap_out_layers.argtypes = [vp, i32p, C.c_int32, vp, C.c_size_t, vp]
+        L.kv_swap_in_layers.argtypes = [vp, i32p, C.c_int32, vp, C.c_size_t, vp]
+        L.ic_swapper_wait_layer.argtypes = [vp, C.c_int32, C.c_int32, vp]
+        L.ic_swapper_sync_layer.argtypes = [vp, C.c_int32, C.c_int32]
+        L.ic_swapper_sync.argtypes = [vp]
+        L.ic_host_alloc.argtypes, L.ic_host_alloc.restype = [C.c_size_t], vp
+        L.ic_host_free.argtypes = [vp]
+        L.ic_swap_limit_tokens.argtypes = [C.c_double, C.c_double, C.c_double]
+        L.ic_swap_limit_tokens.restype = C.c_int64
+        L.ic_swap_schedule.argtypes = [C.c_int64, C.c_int32, i64p, C.c_int64, i64p]
+        L.ic_swap_schedule.restype = C.c_int64
+        other = ("ic_strerror", "kv_block_bytes", "paged_attn_mixed_workspace_bytes", "ic_swapper_staging_bytes",
+                 "ic_host_alloc", "ic_swap_limit_tokens", "ic_swap_schedule")
         for name in EXPORTS:
-            if name not in ("ic_strerror", "kv_block_bytes", "paged_attn_mixed_workspace_bytes"):
+            if name not in other:
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -237,3 +271,104 @@ class KvPool:
         return {KERNEL_NAMES[k]: {"launches": int(st.launches[k]), "total_ms": float(st.total_ms[k]),
                                  "min_ms": float(st.min_ms[k]), "max_ms": float(st.max_ms[k])}
                 for k in range(IC_K_COUNT)}
+
+
+def swap_limit_tokens(t_fwd_s: float, link_bytes_per_s: float, token_bytes: float) -> int:
+    """Swap limit N_i: tokens whose swap takes as long as a forward pass of t_fwd_s seconds."""
+    return int(lib().ic_swap_limit_tokens(float(t_fwd_s), float(link_bytes_per_s), float(token_bytes)))
+
+
+def swap_schedule(total_blocks: int, block_size: int, limits):
+    """Blocks to move in each iteration under per-iteration token limits -> (iterations used, int64 array)."""
+    lim = np.ascontiguousarray(limits, dtype=np.int64)
+    out = np.zeros(lim.shape[0], dtype=np.int64)
+    i64p = C.POINTER(C.c_int64)
+    used = int(lib().ic_swap_schedule(int(total_blocks), int(block_size), lim.ctypes.data_as(i64p),
+                                      lim.shape[0], out.ctypes.data_as(i64p)))
+    return used, out
+
+
+class PinnedBuffer:
+    """Pinned host memory from the library, viewed as a numpy uint8 array."""
+
+    def __init__(self, nbytes: int):
+        self.nbytes = int(nbytes)
+        self.ptr = lib().ic_host_alloc(self.nbytes)
+        if not self.ptr:
+            raise MemoryError(f"ic_host_alloc({self.nbytes}) failed")
+        self.array = np.ctypeslib.as_array((C.c_uint8 * self.nbytes).from_address(self.ptr))
+
+    def close(self):
+        if self.ptr:
+            self.array = None
+            lib().ic_host_free(C.c_void_p(self.ptr))
+            self.ptr = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class LayerSwapper:
+    """Layer-pipelined swap of listed blocks between L same-shaped pools and pinned host memory."""
+
+    def __init__(self, pools, max_blocks: int, staging_ptr: int, staging_bytes: int, num_stages: int = 2):
+        self.pools = list(pools)
+        self.cfg = SwapperCfg(len(self.pools), int(max_blocks), int(num_stages), 0)
+        arr = (C.c_void_p * len(self.pools))(*[p._h for p in self.pools])
+        h = C.c_void_p()
+        rc = lib().ic_swapper_create(C.byref(self.cfg), arr, C.c_void_p(staging_ptr), int(staging_bytes), C.byref(h))
+        if rc != IC_OK:
+            raise InferceptError(rc, "ic_swapper_create")
+        self._h = h
+
+    @staticmethod
+    def staging_bytes(pool, num_layers: int, max_blocks: int, num_stages: int = 2) -> int:
+        cfg = SwapperCfg(int(num_layers), int(max_blocks), int(num_stages), 0)
+        return int(lib().ic_swapper_staging_bytes(C.byref(cfg), pool._h))
+
+    def close(self):
+        if self._h:
+            lib().ic_swapper_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _call(self, fn, name, ids, host_ptr, layer_stride, after_stream, check):
+        ids = _i32(ids)
+        rc = fn(self._h, _ptr(ids), int(ids.shape[0]), C.c_void_p(host_ptr), int(layer_stride),
+                C.c_void_p(after_stream))
+        if check and rc != IC_OK:
+            raise InferceptError(rc, name)
+        return int(rc)
+
+    def swap_out(self, ids, host_ptr: int, layer_stride: int, after_stream: int = 0, check: bool = True) -> int:
+        return self._call(lib().kv_swap_out_layers, "kv_swap_out_layers", ids, host_ptr, layer_stride,
+                          after_stream, check)
+
+    def swap_in(self, ids, host_ptr: int, layer_stride: int, after_stream: int = 0, check: bool = True) -> int:
+        return self._call(lib().kv_swap_in_layers, "kv_swap_in_layers", ids, host_ptr, layer_stride,
+                          after_stream, check)
+
+    def wait_layer(self, direction: int, layer: int, stream: int = 0) -> int:
+        rc = lib().ic_swapper_wait_layer(self._h, int(direction), int(layer), C.c_void_p(stream))
+        if rc != IC_OK:
+            raise InferceptError(rc, "ic_swapper_wait_layer")
+        return rc
+
+    def sync_layer(self, direction: int, layer: int) -> int:
+        rc = lib().ic_swapper_sync_layer(self._h, int(direction), int(layer))
+        if rc != IC_OK:
+            raise InferceptError(rc, "ic_swapper_sync_layer")
+        return rc
+
+    def sync(self):
+        rc = lib().ic_swapper_sync(self._h)
+        if rc != IC_OK:
+            raise InferceptError(rc, "ic_swapper_sync")

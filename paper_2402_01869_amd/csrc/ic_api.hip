@@ -1,7 +1,5 @@
 // C ABI, host-side validation and launch planning for the intercept hot path.
 // See include/infercept_hot.h for the contract of every entry point.
-#include "../../include/infercept_hot.h"
-
 #include <algorithm>
 #include <cstring>
 #include <new>
@@ -51,6 +49,10 @@ struct ic_pool {
   hipEvent_t ev_fork, ev_join;
   ProfState prof;
 };
+
+namespace ic {
+PoolView pool_view(const ic_pool* pool) { return PoolView{pool->cfg, pool->base, pool->bytes, pool->block_bytes}; }
+}  // namespace ic
 
 namespace {
 
@@ -422,8 +424,10 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
   if (rc != IC_OK) return rc;
   plan_fill(desc, ps, (char*)slot->host);
   char* ws = (char*)dev_workspace;
-  if (hipMemcpyAsync(ws, slot->host, ps.image_bytes, hipMemcpyHostToDevice, st) != hipSuccess)
-    return IC_EHIP;
+  {
+    ProfScope ps_(pool, IC_K_UPLOAD, st);
+    if (launch_upload(ws, slot->host, ps.image_bytes, st) != hipSuccess) return IC_EHIP;
+  }
   if (hipEventRecord(slot->ev, st) != hipSuccess) return IC_EHIP;
   slot->pending = true;
 
@@ -529,11 +533,14 @@ static int swap_common(ic_pool* pool, const int32_t* host_ids, int32_t n, const 
     pool->dev_ids_cap = cap;
   }
   StagingSlot* slot = nullptr;
-  rc = acquire_slot(pool, bytes, &slot);
+  const size_t padded = align_up(bytes, 16);
+  rc = acquire_slot(pool, padded, &slot);
   if (rc != IC_OK) return rc;
   std::memcpy(slot->host, host_ids, bytes);
-  if (hipMemcpyAsync(pool->dev_ids, slot->host, bytes, hipMemcpyHostToDevice, st) != hipSuccess)
-    return IC_EHIP;
+  {
+    ProfScope ps_(pool, IC_K_UPLOAD, st);
+    if (launch_upload(pool->dev_ids, slot->host, padded, st) != hipSuccess) return IC_EHIP;
+  }
   if (hipEventRecord(slot->ev, st) != hipSuccess) return IC_EHIP;
   slot->pending = true;
   hipError_t e;

@@ -5,7 +5,18 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "../../include/infercept_hot.h"
+
 namespace ic {
+
+// What other translation units may know of a pool (the struct itself lives with the C ABI).
+struct PoolView {
+  ic_pool_cfg cfg;
+  char* base;          // device address of block 0
+  size_t bytes;        // bytes the caller said are behind base
+  size_t block_bytes;  // K and V of one block
+};
+PoolView pool_view(const ic_pool* pool);
 
 constexpr int kBlockSize = 16;  // tokens per cache block (the only size built)
 constexpr int kRowWaves = 4;    // waves per workgroup of the row kernel
@@ -73,6 +84,8 @@ hipError_t launch_row_persist_slim(const AttnParams& p, int head_dim, int slots,
 hipError_t launch_tile_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st);
 hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_merge_kernel(const AttnParams& p, int head_dim, hipStream_t st);
+// bytes: multiple of 16; pinned_src: pinned host memory (device-visible); dev_dst: device, 16-byte aligned.
+hipError_t launch_upload(void* dev_dst, const void* pinned_src, size_t bytes, hipStream_t st);
 hipError_t launch_pack(const void* pool, void* staging, const int32_t* dev_ids, int32_t n,
                        size_t block_bytes, hipStream_t st);
 hipError_t launch_unpack(void* pool, const void* staging, const int32_t* dev_ids, int32_t n,

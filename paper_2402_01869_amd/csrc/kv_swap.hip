@@ -65,7 +65,26 @@ hipError_t launch_swap(char* pool, char* staging, const int32_t* dev_ids, int32_
   return hipGetLastError();
 }
 
+// Descriptor upload: pinned host memory -> device, 16 bytes per lane, read over the host link by
+// the kernel itself.  Used instead of a DMA copy so that a call's small descriptor never queues
+// behind a bulk transfer on a copy engine (a layer of a swap occupies one for milliseconds) and the
+// kernels that follow need no cross-engine synchronisation.
+__global__ __launch_bounds__(256) void upload_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
+                                                     uint32_t n16) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i < n16) dst[i] = __builtin_nontemporal_load(src + i);
+}
+
 }  // namespace
+
+hipError_t launch_upload(void* dev_dst, const void* pinned_src, size_t bytes, hipStream_t st) {
+  if (bytes == 0) return hipSuccess;
+  if ((bytes & 15u) || bytes > ((size_t)1 << 31)) return hipErrorInvalidValue;
+  const uint32_t n16 = (uint32_t)(bytes / 16);
+  hipLaunchKernelGGL(upload_kernel, dim3((n16 + 255u) / 256u), dim3(256), 0, st, (u32x4*)dev_dst,
+                     (const u32x4*)pinned_src, n16);
+  return hipGetLastError();
+}
 
 hipError_t launch_pack(const void* pool, void* staging, const int32_t* dev_ids, int32_t n,
                        size_t block_bytes, hipStream_t st) {

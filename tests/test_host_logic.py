@@ -149,3 +149,68 @@ def test_full_size_plans_are_sane():
         assert info["tile_items"] >= cfg.n_span * (cfg.span_len // 256)
         assert 0 < p.workspace_bytes(d) < (4 << 30)
         p.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# Layer-pipelined swap: host-side validation and the swap-limit arithmetic (no GPU touched)
+# ---------------------------------------------------------------------------------------------
+def _swapper(L=3, max_blocks=8, stages=2, staging_ptr=0x4000000, staging_bytes=None, pools=None):
+    pools = pools or [_pool(ptr=0x100000 * (l + 1)) for l in range(L)]
+    bb = pools[0].block_bytes
+    nbytes = stages * max_blocks * bb if staging_bytes is None else staging_bytes
+    return B.LayerSwapper(pools, max_blocks, staging_ptr, nbytes, stages), pools
+
+
+def test_swapper_create_validation():
+    sw, pools = _swapper()
+    assert B.LayerSwapper.staging_bytes(pools[0], 3, 8, 2) == 2 * 8 * pools[0].block_bytes
+    sw.close()
+    bad = [(dict(stages=1), B.IC_EINVAL), (dict(stages=9), B.IC_EINVAL), (dict(max_blocks=0), B.IC_EINVAL),
+           (dict(max_blocks=65), B.IC_EINVAL),                       # more than the pool holds
+           (dict(staging_ptr=0x4000008), B.IC_EALIGN), (dict(staging_ptr=0), B.IC_ENULL),
+           (dict(staging_bytes=2 * 8 * 16384 - 1), B.IC_ESIZE),
+           (dict(staging_ptr=0x100000 + 4096), B.IC_EINVAL),         # staging inside layer 0's pool
+           (dict(pools=[_pool(ptr=0x100000), _pool(cfg=B.make_cfg(64, 4, 128), ptr=0x900000)]), B.IC_EINVAL)]
+    for kw, code in bad:
+        with pytest.raises(B.InferceptError) as e:
+            _swapper(**kw)
+        assert e.value.code == code, kw
+
+
+def test_swapper_call_validation_happens_before_any_gpu_work():
+    sw, pools = _swapper()
+    host, stride = 0x7000000, 8 * pools[0].block_bytes
+    for fn in (sw.swap_out, sw.swap_in):
+        assert fn([], host, stride, check=False) == B.IC_OK                     # n = 0: nothing to do
+        assert fn(list(range(9)), host, stride, check=False) == B.IC_EINVAL     # more than max_blocks
+        assert fn([1, 64], host, stride, check=False) == B.IC_ERANGE
+        assert fn([1, -1], host, stride, check=False) == B.IC_ERANGE
+        assert fn([1, 2], 0, stride, check=False) == B.IC_ENULL
+        assert fn([1, 2, 3], host, 2 * pools[0].block_bytes, check=False) == B.IC_ESIZE
+        assert fn([1, 2], host + 4, stride, check=False) == B.IC_EALIGN
+    assert sw.swap_in([5, 5], host, stride, check=False) == B.IC_EDUP            # order-dependent result
+    assert sw.wait_layer(B.IC_SWAP_IN, 2) == B.IC_OK                             # nothing queued: no-op
+    with pytest.raises(B.InferceptError):
+        sw.wait_layer(B.IC_SWAP_IN, 3)
+    with pytest.raises(B.InferceptError):
+        sw.sync_layer(2, 0)
+    sw.sync()
+    sw.close()
+
+
+def test_swap_limit_and_schedule_match_the_oracle():
+    import oracle
+    rng = np.random.default_rng(11)
+    for _ in range(500):
+        t = float(rng.uniform(0, 0.3)); bw = float(rng.uniform(1e9, 2e11)); m = float(rng.integers(512, 8 << 20))
+        assert B.swap_limit_tokens(t, bw, m) == oracle.swap_limit_tokens(t, bw, m)
+    for args in [(0.0, 1e9, 1024.0), (0.5, 2.0 ** 30, 2.0 ** 20), (-1.0, 1e9, 1.0), (1.0, 0.0, 1.0), (1.0, 1.0, 0.0),
+                 (float("nan"), 1e9, 1.0), (1e30, 1e30, 1e-30)]:
+        assert B.swap_limit_tokens(*args) == oracle.swap_limit_tokens(*args), args
+    for _ in range(200):
+        total = int(rng.integers(0, 300)); bs = int(rng.choice([1, 16, 32]))
+        limits = rng.integers(0, 50 * bs, size=int(rng.integers(0, 25))).astype(np.int64)
+        got, want = B.swap_schedule(total, bs, limits), oracle.swap_schedule(total, bs, limits)
+        assert got[0] == want[0] and np.array_equal(got[1], want[1])
+    assert B.swap_schedule(5, 16, [32, -1])[0] == oracle.swap_schedule(5, 16, [32, -1])[0] == -1
+    assert B.swap_schedule(-1, 16, [32])[0] == -1 and B.swap_schedule(1, 0, [32])[0] == -1
