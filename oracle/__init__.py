@@ -6,6 +6,7 @@ package; the product path (paper_2402_01869_amd) never does and shares no code w
 paged_attn / paged_attn_items : textbook causal scaled-dot-product attention read through
     block tables (paper Sections 3.1, 4.2 and 4.3), fp64, bf16 bit patterns in.
 pack_blocks / unpack_blocks   : the swap gather / scatter of Section 3.2 as memcpy loops.
+kv_append                     : a chunk's own keys / values written into the paged cache (Sections 4.2, 4.3).
 swap_out_layers / swap_in_layers / swap_limit_tokens / swap_schedule : what the layer-by-layer,
     chunked swap of Section 4.1 leaves behind, its swap limit N_i and the split over iterations.
 Every function is pinned by tests/test_oracle_pins.py; none is "parity unpinned".
@@ -41,6 +42,9 @@ def lib():
         _lib.oracle_unpack_blocks.argtypes = [u8p, C.c_int64, C.c_int64, i32p, C.c_int64, u8p]
         _lib.oracle_unpack_blocks.restype = C.c_int
         _lib.oracle_num_threads.restype = C.c_int
+        _lib.oracle_kv_append.argtypes = [u16p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p,
+                                          i32p, C.c_int, u16p, u16p]
+        _lib.oracle_kv_append.restype = C.c_int
         vpp, i64p = C.POINTER(C.c_void_p), C.POINTER(C.c_int64)
         _lib.oracle_swap_out_layers.argtypes = [vpp, C.c_int64, C.c_int64, C.c_int64, i32p, C.c_int64, u8p, C.c_int64]
         _lib.oracle_swap_out_layers.restype = C.c_int
@@ -72,7 +76,7 @@ def _check(rc: int) -> None:
     if rc == -2:
         raise OracleError("oracle: invalid descriptor or block id")
     if rc == -3:
-        raise OracleError("oracle: duplicate destination block id")
+        raise OracleError("oracle: duplicate destination (block id or cache slot)")
     if rc != 0:
         raise OracleError(f"oracle: error {rc}")
 
@@ -152,6 +156,23 @@ def unpack_blocks(pool_bytes: np.ndarray, ids, staging: np.ndarray) -> None:
 
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
+
+
+def kv_append(pool_bits: np.ndarray, ctx_len, q_len, q_start, block_tables, k_new, v_new) -> None:
+    """Write rows of k_new / v_new (uint16 [rows][H][D]) into pool_bits (uint16 [blocks][2][H][B][D]) in place:
+    row q_start[s] + i goes to logical position ctx_len[s] - q_len[s] + i of sequence s."""
+    assert pool_bits.dtype == np.uint16 and pool_bits.flags.c_contiguous
+    nblk, two, H, B, D = pool_bits.shape
+    assert two == 2
+    ctx_len, q_len, q_start = _c(ctx_len, np.int32), _c(q_len, np.int32), _c(q_start, np.int32)
+    block_tables = _c(block_tables, np.int32)
+    k_new, v_new = _c(k_new, np.uint16), _c(v_new, np.uint16)
+    assert k_new.shape == v_new.shape and k_new.shape[1:] == (H, D)
+    assert int((q_start + q_len).max()) <= k_new.shape[0]
+    _check(lib().oracle_kv_append(_p(pool_bits, C.c_uint16), nblk, B, H, D, ctx_len.shape[0],
+                                  _p(ctx_len, C.c_int32), _p(q_len, C.c_int32), _p(q_start, C.c_int32),
+                                  _p(block_tables, C.c_int32), block_tables.shape[1],
+                                  _p(k_new, C.c_uint16), _p(v_new, C.c_uint16)))
 
 
 def _layer_ptrs(pools):

@@ -19,6 +19,8 @@
  *    reproduces what a one-shot causal prefill would have produced.
  *  - Swap of scattered blocks (Section 3.2, swap-based approach): gather the
  *    listed blocks into a contiguous staging buffer, and scatter them back.
+ *  - KV append (Sections 4.2, 4.3): the keys and values of a chunk's own
+ *    positions are written into the paged cache before the chunk attends.
  *  - Swap pipelining and chunking (Section 4.1): what a layer-by-layer swap of
  *    the listed blocks leaves in host memory / in the pools (the pipeline only
  *    changes WHEN bytes move, so the result is the per-layer gather / scatter),
@@ -195,6 +197,51 @@ int oracle_unpack_blocks(uint8_t *pool, int64_t num_blocks, int64_t block_bytes,
     free(seen);
     for (int64_t i = 0; i < n; ++i)
         memcpy(pool + (int64_t)ids[i] * block_bytes, staging + i * block_bytes, (size_t)block_bytes);
+    return 0;
+}
+
+/*
+ * KV append (Sections 4.2 and 4.3): before a recomputation chunk (or a decode token) attends, the
+ * keys and values just computed for its q_len[s] query positions enter the cache at logical
+ * positions ctx_len[s] - q_len[s] .. ctx_len[s] - 1 of sequence s, i.e. in block
+ * block_table[t / B], slot t % B, so that the attention of this iteration and the chunks of later
+ * iterations find them there.  k_new / v_new: bf16 bit patterns [total rows][H][D], row
+ * q_start[s] + i belongs to position ctx_len[s] - q_len[s] + i.  Every other slot keeps its bytes.
+ * Returns -2 on an invalid descriptor or block id, -3 if two rows address the same slot.
+ */
+int oracle_kv_append(uint16_t *pool, int64_t num_blocks, int B, int H, int D, int num_seqs,
+                     const int32_t *ctx_len, const int32_t *q_len, const int32_t *q_start,
+                     const int32_t *block_tables, int max_blocks_per_seq, const uint16_t *k_new,
+                     const uint16_t *v_new)
+{
+    if (num_seqs < 0 || B < 1 || H < 1 || D < 1) return -2;
+    uint8_t *seen = (uint8_t *)calloc((size_t)(num_blocks * B > 0 ? num_blocks * B : 1), 1);
+    if (!seen) return -1;
+    for (int s = 0; s < num_seqs; ++s) {                      /* validate everything before writing */
+        if (ctx_len[s] < 1 || q_len[s] < 1 || q_len[s] > ctx_len[s] || q_start[s] < 0 ||
+            (ctx_len[s] + B - 1) / B > max_blocks_per_seq) { free(seen); return -2; }
+        for (int i = 0; i < q_len[s]; ++i) {
+            int t = ctx_len[s] - q_len[s] + i;
+            int32_t blk = block_tables[(int64_t)s * max_blocks_per_seq + t / B];
+            if (blk < 0 || blk >= num_blocks) { free(seen); return -2; }
+            int64_t slot = (int64_t)blk * B + t % B;
+            if (seen[slot]) { free(seen); return -3; }
+            seen[slot] = 1;
+        }
+    }
+    free(seen);
+    for (int s = 0; s < num_seqs; ++s)
+        for (int i = 0; i < q_len[s]; ++i) {
+            int t = ctx_len[s] - q_len[s] + i;
+            int64_t blk = block_tables[(int64_t)s * max_blocks_per_seq + t / B];
+            int64_t row = (int64_t)q_start[s] + i;
+            for (int h = 0; h < H; ++h) {
+                uint16_t *kd = pool + ((((blk * 2 + 0) * H + h) * B) + t % B) * D;
+                uint16_t *vd = pool + ((((blk * 2 + 1) * H + h) * B) + t % B) * D;
+                memcpy(kd, k_new + (row * H + h) * D, sizeof(uint16_t) * (size_t)D);
+                memcpy(vd, v_new + (row * H + h) * D, sizeof(uint16_t) * (size_t)D);
+            }
+        }
     return 0;
 }
 

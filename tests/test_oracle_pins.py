@@ -413,3 +413,81 @@ def test_swap_schedule_respects_limits_and_moves_everything_once():
     # hand example: 10 blocks of 16 tokens under limits 40, 16, 15, 100, 100 tokens -> 2, 1, 0, 6, 1
     used, blocks = oracle.swap_schedule(10, 16, [40, 16, 15, 100, 100])
     assert used == 5 and list(blocks) == [2, 1, 0, 6, 1]
+
+
+# ---------------------------------------------------------------------------------------------
+# KV append (Sections 4.2, 4.3): a chunk's own keys / values enter the paged cache before it attends
+# ---------------------------------------------------------------------------------------------
+def _append_case(seed, H=3, D=16, nb=40, ctx=(50, 17, 33, 16), qlen=(20, 1, 33, 5)):
+    rng = np.random.default_rng(seed)
+    batch = W.assemble_batch(H, D, B, nb, list(ctx), list(qlen), rng)
+    pool = W.randn_bf16(W.pool_shape(nb, H, B, D), rng)
+    k_new = W.randn_bf16((batch.total_q_rows, H, D), rng)
+    v_new = W.randn_bf16((batch.total_q_rows, H, D), rng)
+    return batch, pool, k_new, v_new
+
+
+def test_kv_append_equals_slot_by_slot_numpy_writes_and_touches_nothing_else():
+    # Catches: K/V planes swapped, position off by one, slot/block index transposed, head stride wrong.
+    batch, pool, k_new, v_new = _append_case(21)
+    want = pool.copy()
+    touched = np.zeros(pool.shape[:1] + pool.shape[3:4], dtype=bool)           # [block][slot]
+    for s in range(batch.num_seqs):
+        for i in range(int(batch.q_len[s])):
+            t = int(batch.ctx_len[s] - batch.q_len[s]) + i
+            blk = int(batch.block_tables[s, t // B])
+            want[blk, 0, :, t % B, :] = k_new[batch.q_start[s] + i]
+            want[blk, 1, :, t % B, :] = v_new[batch.q_start[s] + i]
+            touched[blk, t % B] = True
+    got = pool.copy()
+    oracle.kv_append(got, batch.ctx_len, batch.q_len, batch.q_start, batch.block_tables, k_new, v_new)
+    assert np.array_equal(got, want)
+    keep = ~touched
+    assert np.array_equal(got.transpose(0, 3, 1, 2, 4)[keep], pool.transpose(0, 3, 1, 2, 4)[keep])
+    assert touched.sum() == batch.total_q_rows
+
+
+def test_kv_append_then_attention_equals_dense_attention_on_the_new_keys():
+    # The appended rows must be exactly what attention then reads at those positions: append K/V for the
+    # chunk, run the paged oracle, compare with dense attention on prefix + chunk (independent numpy).
+    rng = np.random.default_rng(22)
+    H, D, ctx, n = 2, 32, 77, 30
+    K = W.randn_bf16((ctx, H, D), rng); V = W.randn_bf16((ctx, H, D), rng); q = W.randn_bf16((n, H, D), rng)
+    table = rng.permutation(12)[:-(-ctx // B)].astype(np.int32)
+    Kp, Vp = K.copy(), V.copy()
+    Kp[ctx - n:] = 0x7FFF; Vp[ctx - n:] = 0x7FFF                               # chunk positions not yet written
+    pool = paged_pool_from_dense(Kp, Vp, table, B, 12)
+    oracle.kv_append(pool, [ctx], [n], [0], table[None, :], K[ctx - n:], V[ctx - n:])
+    out = oracle.paged_attn(pool, [ctx], [n], [0], table[None, :], q, 0.2)
+    want = dense_causal_attention(W.bf16_bits_to_f64(q), W.bf16_bits_to_f64(K), W.bf16_bits_to_f64(V), 0.2, ctx - n)
+    assert np.abs(out - want).max() < 1e-12
+
+
+@pytest.mark.parametrize("chunk", [1, 7, 16, 40])
+def test_kv_append_chunk_by_chunk_equals_one_shot(chunk):
+    # Section 4.3: a context recomputed over several iterations ends up with the same cache.
+    rng = np.random.default_rng(23)
+    H, D, L = 2, 16, 40
+    table = rng.permutation(8)[:3].astype(np.int32)
+    K = W.randn_bf16((L, H, D), rng); V = W.randn_bf16((L, H, D), rng)
+    one = np.zeros(W.pool_shape(8, H, B, D), dtype=np.uint16)
+    oracle.kv_append(one, [L], [L], [0], table[None, :], K, V)
+    step = np.zeros_like(one)
+    for a in range(0, L, chunk):
+        b = min(L, a + chunk)
+        oracle.kv_append(step, [b], [b - a], [0], table[None, :], K[a:b], V[a:b])
+    assert np.array_equal(one, step)
+    assert np.array_equal(one, paged_pool_from_dense(K, V, table, B, 8, fill_bits=0))
+
+
+def test_kv_append_rejects_bad_descriptors_and_shared_slots():
+    batch, pool, k_new, v_new = _append_case(24)
+    before = pool.copy()
+    bt = batch.block_tables.copy(); bt[0, 3] = 40
+    with pytest.raises(oracle.OracleError):
+        oracle.kv_append(pool, batch.ctx_len, batch.q_len, batch.q_start, bt, k_new, v_new)
+    bt = batch.block_tables.copy(); bt[1, 1] = bt[3, 0]; bt[1, 0] = bt[1, 0]    # seq 1 (pos 16) and seq 3 share a block
+    ctx = batch.ctx_len.copy(); ctx[3] = 5; ql = batch.q_len.copy(); ql[3] = 5  # seq 3 writes slots 0..4 of it
+    with pytest.raises(oracle.OracleError):
+        oracle.kv_append(pool, ctx, ql, batch.q_start, bt, k_new, v_new)        # slot 0 addressed twice
+    assert np.array_equal(pool, before), "a rejected call must not write"
