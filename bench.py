@@ -49,6 +49,7 @@ def parse_args():
     ap.add_argument("--stages", type=int, default=2, help="swap_pipeline: staging buffers")
     ap.add_argument("--no-swap", action="store_true", help="time the attention call only")
     ap.add_argument("--decode-only", action="store_true", help="drop the recomputation spans from the batch")
+    ap.add_argument("--no-append", action="store_true", help="skip the kv_write_span timing after the steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="target oracle time for the CPU sample")
     return ap.parse_args()
@@ -390,6 +391,29 @@ def main():
     decode_alone_ms = sub_call_ms(lambda b: b.q_len == 1)
     spans_alone_ms = sub_call_ms(lambda b: b.q_len > 1)
 
+    # ---- loop 5 (outside the step): kv_write_span of the same batches, the step that precedes the
+    # attention call in an iteration; the rows written are random, the pool is refilled by nothing:
+    # attention outputs above were already taken.
+    append = None
+    if not args.no_append:
+        kn = [torch.randn((b.total_q_rows, H, D), device=dev).to(torch.bfloat16) for b in batches]
+        vn = [torch.randn((b.total_q_rows, H, D), device=dev).to(torch.bfloat16) for b in batches]
+        n_ap = max(10, args.steps // 2)
+        for timed in (False, True):
+            if timed:
+                pool.prof_begin(2 * n_ap + 8)
+            for i in range(n_ap):
+                k = i & 1
+                pool.kv_write_span(descs[k], kn[k].data_ptr(), vn[k].data_ptr(), stream)
+            torch.cuda.synchronize()
+        ap = pool.prof_end()["append"]
+        ap_ms = ap["total_ms"] / ap["launches"]
+        ap_bytes = float(np.mean([2.0 * 2 * b.total_q_rows * H * D * 2 for b in batches]))   # K and V, read + write
+        append = {"rows": int(np.mean([b.total_q_rows for b in batches])), "moved_bytes": ap_bytes,
+                  "avg_ms": round(ap_ms, 5), "min_ms": round(ap["min_ms"], 5),
+                  "GBps": round(ap_bytes / (ap_ms * 1e-3) / 1e9, 1),
+                  "frac_hbm_peak": round(ap_bytes / (ap_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+
     kv_bytes = float(np.mean([b.kv_bytes() for b in batches]))
     dec_bytes = float(np.mean([int(b.ctx_len[b.q_len == 1].astype(np.int64).sum()) * b.token_bytes for b in batches]))
     span_flops = float(np.mean([b.span_flops() for b in batches]))
@@ -463,6 +487,8 @@ def main():
         for k in ("pack", "unpack"):
             g = swap_moved / (avg_ms(k) * 1e-3) / 1e9
             result[k] = {"moved_bytes": swap_moved, "GBps": round(g, 1), "frac_hbm_peak": round(g / HBM_PEAK_GBPS, 4)}
+    if append:
+        result["kv_write_span"] = append
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(batches[0], pool_t, qs[0][1], args.cpu_seconds)
     print(json.dumps(result))

@@ -119,6 +119,21 @@ size_t paged_attn_mixed_workspace_bytes(const ic_pool* pool, const ic_batch_desc
 int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q, void* dev_out,
                      void* dev_workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * KV append (Section 4.2: a recomputation chunk joins the batch; Section 4.3: a partly recomputed
+ * request continues in later iterations, so what one chunk computes must be in the cache for the
+ * next).  Writes the keys and values computed for this iteration's query positions into the paged
+ * cache: for every sequence s and row i < q_len[s], position t = ctx_len[s] - q_len[s] + i,
+ *      pool[block_tables[s][t / block_size]][K|V][h][t % block_size][:] = k_new|v_new[q_start[s] + i][h][:]
+ * for decode sequences (q_len = 1: the new token) and chunks alike.  It is the step before
+ * paged_attn_mixed on the same descriptor, on the same stream.  dev_k_new, dev_v_new: device bf16
+ * [total_q_rows][num_kv_heads][head_dim]; rows no sequence owns are ignored.  Byte-exact; every
+ * other slot of the cache keeps its bytes.  Two rows that address one slot (sequences sharing a
+ * block they both write) give IC_EDUP; IC_FLAG_TRUSTED skips that check and the id checks.
+ */
+int kv_write_span(ic_pool* pool, const ic_batch_desc* desc, const void* dev_k_new, const void* dev_v_new,
+                  void* hip_stream);
+
 /* Host-only validation of a descriptor against a pool shape (what paged_attn_mixed checks when
  * IC_FLAG_TRUSTED is clear).  Touches no GPU state. */
 int ic_check_batch(const ic_pool_cfg* cfg, const ic_batch_desc* desc);
@@ -248,7 +263,7 @@ int64_t ic_swap_schedule(int64_t total_blocks, int32_t block_size, const int64_t
  * ic_prof_begin and ic_prof_end every kernel the pool launches is bracketed by an event pair.
  * ic_prof_end synchronises the recorded events and returns totals per kernel kind.
  * ------------------------------------------------------------------------------------------ */
-enum { IC_K_ROW = 0, IC_K_TILE = 1, IC_K_MERGE = 2, IC_K_PACK = 3, IC_K_UNPACK = 4, IC_K_UPLOAD = 5, IC_K_COUNT = 6 };
+enum { IC_K_ROW = 0, IC_K_TILE = 1, IC_K_MERGE = 2, IC_K_PACK = 3, IC_K_UNPACK = 4, IC_K_UPLOAD = 5, IC_K_APPEND = 6, IC_K_COUNT = 7 };
 /* IC_K_UPLOAD: the kernel that copies a call's descriptor from pinned host memory to the device. */
 typedef struct {
   int32_t launches[IC_K_COUNT];

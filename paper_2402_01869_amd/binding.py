@@ -19,8 +19,8 @@ IC_OK = 0
 IC_ENULL, IC_EINVAL, IC_ERANGE, IC_ESIZE, IC_EALIGN = -1, -2, -3, -4, -5
 IC_EDUP, IC_EUNSUPPORTED, IC_EOVERLAP, IC_EHIP, IC_ENOMEM = -6, -7, -8, -9, -10
 IC_FLAG_TRUSTED = 1
-IC_K_ROW, IC_K_TILE, IC_K_MERGE, IC_K_PACK, IC_K_UNPACK, IC_K_UPLOAD, IC_K_COUNT = 0, 1, 2, 3, 4, 5, 6
-KERNEL_NAMES = ("row", "tile", "merge", "pack", "unpack", "upload")
+IC_K_ROW, IC_K_TILE, IC_K_MERGE, IC_K_PACK, IC_K_UNPACK, IC_K_UPLOAD, IC_K_APPEND, IC_K_COUNT = 0, 1, 2, 3, 4, 5, 6, 7
+KERNEL_NAMES = ("row", "tile", "merge", "pack", "unpack", "upload", "append")
 
 EXPORTS = (
     "ic_strerror", "kv_pool_init", "kv_pool_destroy", "kv_block_bytes",
@@ -29,7 +29,7 @@ EXPORTS = (
     "ic_prof_end",
     "ic_swapper_staging_bytes", "ic_swapper_create", "ic_swapper_destroy", "kv_swap_out_layers",
     "kv_swap_in_layers", "ic_swapper_wait_layer", "ic_swapper_sync_layer", "ic_swapper_sync",
-    "ic_host_alloc", "ic_host_free", "ic_swap_limit_tokens", "ic_swap_schedule",
+    "ic_host_alloc", "ic_host_free", "ic_swap_limit_tokens", "ic_swap_schedule", "kv_write_span",
 )
 IC_SWAP_OUT, IC_SWAP_IN = 0, 1
 
@@ -104,6 +104,7 @@ def lib():
         L.paged_attn_mixed_workspace_bytes.argtypes = [vp, C.POINTER(BatchDesc)]
         L.paged_attn_mixed_workspace_bytes.restype = C.c_size_t
         L.paged_attn_mixed.argtypes = [vp, C.POINTER(BatchDesc), vp, vp, vp, C.c_size_t, vp]
+        L.kv_write_span.argtypes = [vp, C.POINTER(BatchDesc), vp, vp, vp]
         L.ic_check_batch.argtypes = [C.POINTER(PoolCfg), C.POINTER(BatchDesc)]
         L.ic_pool_set_tuning.argtypes = [vp, C.POINTER(Tuning)]
         L.ic_plan_query.argtypes = [vp, C.POINTER(BatchDesc), C.POINTER(PlanInfo)]
@@ -240,6 +241,12 @@ class KvPool:
                                     C.c_void_p(ws_ptr), int(ws_bytes), C.c_void_p(stream))
         if check and rc != IC_OK:
             raise InferceptError(rc, "paged_attn_mixed")
+        return int(rc)
+
+    def kv_write_span(self, desc: HostDesc, k_ptr: int, v_ptr: int, stream: int = 0, check: bool = True) -> int:
+        rc = lib().kv_write_span(self._h, C.byref(desc.struct), C.c_void_p(k_ptr), C.c_void_p(v_ptr), C.c_void_p(stream))
+        if check and rc != IC_OK:
+            raise InferceptError(rc, "kv_write_span")
         return int(rc)
 
     def kv_pack_blocks(self, ids, staging_ptr: int, staging_bytes: int, stream: int = 0, check: bool = True) -> int:

@@ -503,6 +503,22 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
   return IC_OK;
 }
 
+// The pool's device-side int32 list (block ids of a swap, row destinations of an append).
+static int ensure_dev_ids(ic_pool* pool, size_t bytes) {
+  if (pool->dev_ids_cap >= bytes) return IC_OK;
+  // Growing the buffer: earlier launches may still read the old one.
+  if (pool->dev_ids) {
+    if (hipDeviceSynchronize() != hipSuccess) return IC_EHIP;
+    (void)hipFree(pool->dev_ids);
+    pool->dev_ids = nullptr;
+    pool->dev_ids_cap = 0;
+  }
+  const size_t cap = align_up(std::max(bytes, (size_t)1 << 16), 4096);
+  if (hipMalloc((void**)&pool->dev_ids, cap) != hipSuccess) return IC_EHIP;
+  pool->dev_ids_cap = cap;
+  return IC_OK;
+}
+
 static int swap_common(ic_pool* pool, const int32_t* host_ids, int32_t n, const void* dev_staging,
                        size_t staging_bytes, void* hip_stream, bool pack) {
   if (!pool) return IC_ENULL;
@@ -520,18 +536,7 @@ static int swap_common(ic_pool* pool, const int32_t* host_ids, int32_t n, const 
   }
   hipStream_t st = (hipStream_t)hip_stream;
   const size_t bytes = sizeof(int32_t) * (size_t)n;
-  if (pool->dev_ids_cap < bytes) {
-    // Growing the id buffer: earlier launches may still read the old one.
-    if (pool->dev_ids) {
-      if (hipDeviceSynchronize() != hipSuccess) return IC_EHIP;
-      (void)hipFree(pool->dev_ids);
-      pool->dev_ids = nullptr;
-      pool->dev_ids_cap = 0;
-    }
-    const size_t cap = align_up(std::max(bytes, (size_t)1 << 16), 4096);
-    if (hipMalloc((void**)&pool->dev_ids, cap) != hipSuccess) return IC_EHIP;
-    pool->dev_ids_cap = cap;
-  }
+  if ((rc = ensure_dev_ids(pool, bytes)) != IC_OK) return rc;
   StagingSlot* slot = nullptr;
   const size_t padded = align_up(bytes, 16);
   rc = acquire_slot(pool, padded, &slot);
@@ -560,6 +565,53 @@ int kv_pack_blocks(ic_pool* pool, const int32_t* host_ids, int32_t n, void* dev_
 int kv_unpack_blocks(ic_pool* pool, const int32_t* host_ids, int32_t n, const void* dev_staging,
                      size_t staging_bytes, void* hip_stream) {
   return swap_common(pool, host_ids, n, dev_staging, staging_bytes, hip_stream, false);
+}
+
+int kv_write_span(ic_pool* pool, const ic_batch_desc* desc, const void* dev_k_new, const void* dev_v_new,
+                  void* hip_stream) {
+  if (!pool || !desc || !dev_k_new || !dev_v_new) return IC_ENULL;
+  const bool trusted = (desc->flags & IC_FLAG_TRUSTED) != 0;
+  int rc = check_batch(pool->cfg, desc, trusted);
+  if (rc != IC_OK) return rc;
+  if (misaligned(dev_k_new) || misaligned(dev_v_new)) return IC_EALIGN;
+  // destination of every row: block * block_size + slot, or -1 for rows no sequence owns
+  const size_t rows = (size_t)desc->total_q_rows;
+  const size_t bytes = align_up(sizeof(int32_t) * rows, 16);
+  std::vector<int32_t> dst(bytes / sizeof(int32_t), -1);
+  for (int s = 0; s < desc->num_seqs; ++s) {
+    const int32_t* table = desc->block_tables + (int64_t)s * desc->max_blocks_per_seq;
+    const int t0 = desc->ctx_len[s] - desc->q_len[s];
+    for (int i = 0; i < desc->q_len[s]; ++i) {
+      const int t = t0 + i;
+      dst[desc->q_start[s] + i] = table[t / kBlockSize] * kBlockSize + t % kBlockSize;
+    }
+  }
+  if (!trusted) {  // two rows on one slot would make the result depend on the order of the writes
+    std::vector<uint8_t> seen((size_t)pool->cfg.num_blocks * kBlockSize, 0);
+    for (size_t r = 0; r < rows; ++r) {
+      if (dst[r] < 0) continue;
+      if (seen[dst[r]]) return IC_EDUP;
+      seen[dst[r]] = 1;
+    }
+  }
+  if ((rc = ensure_dev_ids(pool, bytes)) != IC_OK) return rc;
+  StagingSlot* slot = nullptr;
+  if ((rc = acquire_slot(pool, bytes, &slot)) != IC_OK) return rc;
+  std::memcpy(slot->host, dst.data(), bytes);
+  hipStream_t st = (hipStream_t)hip_stream;
+  {
+    ProfScope ps_(pool, IC_K_UPLOAD, st);
+    if (launch_upload(pool->dev_ids, slot->host, bytes, st) != hipSuccess) return IC_EHIP;
+  }
+  if (hipEventRecord(slot->ev, st) != hipSuccess) return IC_EHIP;
+  slot->pending = true;
+  hipError_t e;
+  {
+    ProfScope ps_(pool, IC_K_APPEND, st);
+    e = launch_append(pool->base, dev_k_new, dev_v_new, pool->dev_ids, desc->total_q_rows, pool->cfg.num_kv_heads,
+                      pool->cfg.head_dim, st);
+  }
+  return e == hipSuccess ? IC_OK : IC_EHIP;
 }
 
 int ic_prof_begin(ic_pool* pool, int32_t max_launches) {

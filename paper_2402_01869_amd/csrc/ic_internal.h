@@ -84,6 +84,9 @@ hipError_t launch_row_persist_slim(const AttnParams& p, int head_dim, int slots,
 hipError_t launch_tile_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st);
 hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_merge_kernel(const AttnParams& p, int head_dim, hipStream_t st);
+// Rows of k_new / v_new ([rows][H][D] bf16) into the pool at slot dst[row] (block * 16 + slot; < 0: skip).
+hipError_t launch_append(void* pool, const void* k_new, const void* v_new, const int32_t* dev_dst, int32_t rows,
+                         int num_heads, int head_dim, hipStream_t st);
 // bytes: multiple of 16; pinned_src: pinned host memory (device-visible); dev_dst: device, 16-byte aligned.
 hipError_t launch_upload(void* dev_dst, const void* pinned_src, size_t bytes, hipStream_t st);
 hipError_t launch_pack(const void* pool, void* staging, const int32_t* dev_ids, int32_t n,

@@ -75,7 +75,49 @@ __global__ __launch_bounds__(256) void upload_kernel(u32x4* __restrict__ dst, co
   if (i < n16) dst[i] = __builtin_nontemporal_load(src + i);
 }
 
+// KV append: the keys and values a chunk (or a decode token) has just computed for its own positions
+// enter the paged cache (Sections 4.2, 4.3).  One lane moves 16 bytes; consecutive lanes read
+// consecutive bytes of a row of k_new (then v_new) and write D * 2 contiguous bytes per head into
+// the (block, K/V, head) tile at the row's slot.
+template <int D>
+__global__ __launch_bounds__(kThreads) void kv_append_kernel(char* __restrict__ pool, const char* __restrict__ k_new,
+                                                        const char* __restrict__ v_new,
+                                                        const int32_t* __restrict__ dst, uint32_t rows,
+                                                        uint32_t num_heads) {
+  constexpr uint32_t kChunksPerHead = D / 8;                  // 16-byte chunks of one head's vector
+  const uint32_t per_plane = num_heads * kChunksPerHead;      // chunks of one row of K (or V)
+  const uint64_t idx = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  const uint32_t row = (uint32_t)(idx / (2u * per_plane));
+  if (row >= rows) return;
+  const uint32_t rem = (uint32_t)(idx - (uint64_t)row * (2u * per_plane));
+  const uint32_t kv = rem / per_plane;
+  const uint32_t c = rem - kv * per_plane;
+  const uint32_t h = c / kChunksPerHead, cc = c % kChunksPerHead;
+  const int32_t d = dst[row];
+  if (d < 0) return;
+  const uint32_t blk = (uint32_t)d / (uint32_t)kBlockSize, slot = (uint32_t)d % (uint32_t)kBlockSize;
+  const char* src = (kv ? v_new : k_new) + ((uint64_t)row * per_plane + c) * 16u;
+  char* out = pool + ((((uint64_t)blk * 2u + kv) * num_heads + h) * kBlockSize + slot) * (D * 2) + cc * 16u;
+  __builtin_nontemporal_store(__builtin_nontemporal_load((const u32x4*)src), (u32x4*)out);
+}
+
 }  // namespace
+
+hipError_t launch_append(void* pool, const void* k_new, const void* v_new, const int32_t* dev_dst, int32_t rows,
+                         int num_heads, int head_dim, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  const uint64_t lanes = (uint64_t)rows * 2u * (uint64_t)num_heads * (uint64_t)(head_dim / 8);
+  const uint64_t grid = (lanes + kThreads - 1) / kThreads;  // one-wave workgroups, as for the block moves
+  if (grid > 0x7fffffffull) return hipErrorInvalidValue;
+  const dim3 g((uint32_t)grid), b(kThreads);
+  switch (head_dim) {
+    case 64: hipLaunchKernelGGL(kv_append_kernel<64>, g, b, 0, st, (char*)pool, (const char*)k_new, (const char*)v_new, dev_dst, (uint32_t)rows, (uint32_t)num_heads); break;
+    case 128: hipLaunchKernelGGL(kv_append_kernel<128>, g, b, 0, st, (char*)pool, (const char*)k_new, (const char*)v_new, dev_dst, (uint32_t)rows, (uint32_t)num_heads); break;
+    case 256: hipLaunchKernelGGL(kv_append_kernel<256>, g, b, 0, st, (char*)pool, (const char*)k_new, (const char*)v_new, dev_dst, (uint32_t)rows, (uint32_t)num_heads); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
 
 hipError_t launch_upload(void* dev_dst, const void* pinned_src, size_t bytes, hipStream_t st) {
   if (bytes == 0) return hipSuccess;

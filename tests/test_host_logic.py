@@ -214,3 +214,22 @@ def test_swap_limit_and_schedule_match_the_oracle():
         assert got[0] == want[0] and np.array_equal(got[1], want[1])
     assert B.swap_schedule(5, 16, [32, -1])[0] == oracle.swap_schedule(5, 16, [32, -1])[0] == -1
     assert B.swap_schedule(-1, 16, [32])[0] == -1 and B.swap_schedule(1, 0, [32])[0] == -1
+
+
+def test_kv_write_span_validation_happens_before_any_gpu_work():
+    p = _pool()
+    b = W.make_batch(W.TINY)
+    ok = B.HostDesc.from_batch(b)
+    k = v = 0x9000000
+    assert p.kv_write_span(ok, 0, v, check=False) == B.IC_ENULL
+    assert p.kv_write_span(ok, k, v + 8, check=False) == B.IC_EALIGN
+    bt = b.block_tables.copy(); bt[2, 0] = 64
+    bad = B.HostDesc(b.ctx_len, b.q_len, b.q_start, bt, b.scale, b.total_q_rows)
+    assert p.kv_write_span(bad, k, v, check=False) == B.IC_ERANGE
+    # two sequences whose new tokens land on one slot: the result would depend on the write order
+    s0, s1 = [s for s in range(b.num_seqs) if b.q_len[s] == 1][:2]
+    ctx = b.ctx_len.copy(); ctx[s1] = ctx[s0]
+    bt = b.block_tables.copy(); bt[s1] = bt[s0]
+    dup = B.HostDesc(ctx, b.q_len, b.q_start, bt, b.scale, b.total_q_rows)
+    assert p.kv_write_span(dup, k, v, check=False) == B.IC_EDUP
+    p.close()
