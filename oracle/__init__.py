@@ -7,6 +7,8 @@ paged_attn / paged_attn_items : textbook causal scaled-dot-product attention rea
     block tables (paper Sections 3.1, 4.2 and 4.3), fp64, bf16 bit patterns in.
 pack_blocks / unpack_blocks   : the swap gather / scatter of Section 3.2 as memcpy loops.
 kv_append                     : a chunk's own keys / values written into the paged cache (Sections 4.2, 4.3).
+tfwd / waste_* / chunk_* / saturation_point / schedule_intercepted : the GPU-memory-waste model
+    (Eq. 1-5), the saturation point and the interception schedule (Sections 3.2, 4.2, 4.3).
 swap_out_layers / swap_in_layers / swap_limit_tokens / swap_schedule : what the layer-by-layer,
     chunked swap of Section 4.1 leaves behind, its swap limit N_i and the split over iterations.
 Every function is pinned by tests/test_oracle_pins.py; none is "parity unpinned".
@@ -46,6 +48,20 @@ def lib():
                                           i32p, C.c_int, u16p, u16p]
         _lib.oracle_kv_append.restype = C.c_int
         vpp, i64p = C.POINTER(C.c_void_p), C.POINTER(C.c_int64)
+        dbl = C.c_double
+        _lib.oracle_tfwd.argtypes, _lib.oracle_tfwd.restype = [f64p, f64p, C.c_int, dbl], dbl
+        _lib.oracle_waste_discard.argtypes = [f64p, f64p, C.c_int, dbl, dbl, dbl]
+        _lib.oracle_waste_discard.restype = dbl
+        _lib.oracle_waste_preserve.argtypes, _lib.oracle_waste_preserve.restype = [dbl, dbl, dbl], dbl
+        _lib.oracle_waste_swap.argtypes, _lib.oracle_waste_swap.restype = [dbl, dbl, dbl], dbl
+        _lib.oracle_waste_chunked_discard.argtypes = [f64p, f64p, C.c_int, dbl, dbl, dbl, C.c_int]
+        _lib.oracle_waste_chunked_discard.restype = dbl
+        _lib.oracle_chunk_tokens.argtypes, _lib.oracle_chunk_tokens.restype = [C.c_int64, C.c_int64], C.c_int64
+        _lib.oracle_chunk_count.argtypes, _lib.oracle_chunk_count.restype = [C.c_int64, C.c_int64], C.c_int64
+        _lib.oracle_saturation_point.argtypes = [f64p, f64p, C.c_int, dbl]
+        _lib.oracle_saturation_point.restype = C.c_int64
+        _lib.oracle_schedule_intercepted.argtypes = [C.c_int, f64p, f64p, i64p, C.c_int64, i64p, i32p]
+        _lib.oracle_schedule_intercepted.restype = C.c_int
         _lib.oracle_swap_out_layers.argtypes = [vpp, C.c_int64, C.c_int64, C.c_int64, i32p, C.c_int64, u8p, C.c_int64]
         _lib.oracle_swap_out_layers.restype = C.c_int
         _lib.oracle_swap_in_layers.argtypes = [vpp, C.c_int64, C.c_int64, C.c_int64, i32p, C.c_int64, u8p, C.c_int64]
@@ -215,3 +231,61 @@ def swap_schedule(total_blocks: int, block_size: int, limits) -> tuple:
     used = int(lib().oracle_swap_schedule(int(total_blocks), int(block_size), _p(limits, C.c_int64),
                                           limits.shape[0], _p(out, C.c_int64)))
     return used, out
+
+
+class TfwdTable:
+    """Profiled T_fwd: (tokens, seconds) points, tokens strictly increasing."""
+
+    def __init__(self, tokens, seconds):
+        self.tokens, self.seconds = _c(tokens, np.float64), _c(seconds, np.float64)
+        assert self.tokens.shape == self.seconds.shape and self.tokens.ndim == 1
+
+    def args(self):
+        return _p(self.tokens, C.c_double), _p(self.seconds, C.c_double), int(self.tokens.shape[0])
+
+
+def tfwd(table: TfwdTable, x: float) -> float:
+    return float(lib().oracle_tfwd(*table.args(), float(x)))
+
+
+def waste_discard(table: TfwdTable, C_tokens, C_other, M) -> float:
+    return float(lib().oracle_waste_discard(*table.args(), float(C_tokens), float(C_other), float(M)))
+
+
+def waste_preserve(T_int, C_tokens, M) -> float:
+    return float(lib().oracle_waste_preserve(float(T_int), float(C_tokens), float(M)))
+
+
+def waste_swap(T_swap, C_batch, M) -> float:
+    return float(lib().oracle_waste_swap(float(T_swap), float(C_batch), float(M)))
+
+
+def waste_chunked_discard(table: TfwdTable, C_tokens, C_other, M, n_chunks: int) -> float:
+    return float(lib().oracle_waste_chunked_discard(*table.args(), float(C_tokens), float(C_other), float(M),
+                                                    int(n_chunks)))
+
+
+def chunk_tokens(S: int, running: int) -> int:
+    return int(lib().oracle_chunk_tokens(int(S), int(running)))
+
+
+def chunk_count(C_tokens: int, chunk: int) -> int:
+    return int(lib().oracle_chunk_count(int(C_tokens), int(chunk)))
+
+
+def saturation_point(q_tokens, seconds, frac: float = 0.95) -> int:
+    q, t = _c(q_tokens, np.float64), _c(seconds, np.float64)
+    return int(lib().oracle_saturation_point(_p(q, C.c_double), _p(t, C.c_double), int(q.shape[0]), float(frac)))
+
+
+def schedule_intercepted(waste_preserve_, waste_chunkd, ctx_tokens, budget: int):
+    """-> (swap_tokens int64 [n], action int32 [n]: 0 nothing left, 1 preserve, 2 discard)."""
+    wp, wc = _c(waste_preserve_, np.float64), _c(waste_chunkd, np.float64)
+    ct = _c(ctx_tokens, np.int64)
+    n = int(ct.shape[0])
+    sw, act = np.zeros(n, dtype=np.int64), np.zeros(n, dtype=np.int32)
+    rc = lib().oracle_schedule_intercepted(n, _p(wp, C.c_double), _p(wc, C.c_double), _p(ct, C.c_int64), int(budget),
+                                           _p(sw, C.c_int64), _p(act, C.c_int32))
+    if rc != 0:
+        raise OracleError("oracle: bad schedule arguments")
+    return sw, act

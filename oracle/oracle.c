@@ -27,6 +27,9 @@
  *    the swap limit N_i that solves T_swap(N_i) = T_fwd(B_i), and the split of
  *    one sequence's swap over iterations under those limits.
  *
+ *  - The GPU-memory-waste model (Eq. 1-5), the saturation point and the
+ *    interception schedule (Sections 3.2, 4.2, 4.3).
+ *
  * The attention formula itself is not printed in the paper (it inherits the
  * serving stack's kernels, Section 4.5); it is the standard scaled dot-product
  * causal attention  out = softmax(scale * q K^T) V.
@@ -313,6 +316,121 @@ int64_t oracle_swap_schedule(int64_t total_blocks, int64_t block_size, const int
         if (left == 0) { for (int64_t j = i + 1; j < n_iters; ++j) out_blocks[j] = 0; break; }
     }
     return left > 0 ? n_iters + 1 : used;
+}
+
+/* =====================================================================================
+ * GPU-memory-waste model (Section 3.2: Eq. 1 discard, Eq. 2 preserve, Eq. 3 swap; Section 4.2:
+ * Eq. 4 chunked discard; Section 4.3: Eq. 5 and the interception schedule) and the saturation
+ * point S of Section 4.2.  All in fp64, each function the printed formula.
+ *
+ * T_fwd ("a mapping from the number of scheduled tokens in a batch to the execution time of
+ * that iteration", obtained by offline profiling) is given as n measured points
+ * (tokens[k], seconds[k]), tokens strictly increasing and positive.  Reading (the paper does not
+ * say how the mapping is evaluated between profiled points): straight lines between
+ * neighbouring points, the line through the origin and the first point below it, the last
+ * segment's line beyond the last point (the first point's ray if n = 1).  NaN on a bad table.
+ * ===================================================================================== */
+double oracle_tfwd(const double *tokens, const double *seconds, int n, double x)
+{
+    if (n < 1 || !(x >= 0.0)) return NAN;
+    for (int k = 0; k < n; ++k)
+        if (!(tokens[k] > 0.0) || !(seconds[k] >= 0.0) || (k > 0 && !(tokens[k] > tokens[k - 1]))) return NAN;
+    if (x <= tokens[0] || n == 1) return seconds[0] * (x / tokens[0]);
+    int k = 1;
+    while (k < n - 1 && x > tokens[k]) ++k;          /* segment [k-1, k]; the last one also serves beyond */
+    double w = (x - tokens[k - 1]) / (tokens[k] - tokens[k - 1]);
+    return seconds[k - 1] + w * (seconds[k] - seconds[k - 1]);
+}
+
+/* Eq. 1: recomputing C tokens in one iteration wastes their own memory and everybody else's
+ * (C_other tokens) for T_fwd(C). */
+double oracle_waste_discard(const double *tokens, const double *seconds, int n, double C, double C_other, double M)
+{
+    double t = oracle_tfwd(tokens, seconds, n, C);
+    return t * C * M + t * C_other * M;
+}
+
+/* Eq. 2: a preserved context of C tokens is idle for the interception's duration. */
+double oracle_waste_preserve(double T_int, double C, double M) { return T_int * C * M; }
+
+/* Eq. 3: a synchronous swap stalls the whole batch (C_batch tokens) for T_swap, out and in. */
+double oracle_waste_swap(double T_swap, double C_batch, double M) { return 2.0 * T_swap * C_batch * M; }
+
+/* Eq. 4: recomputation in n chunks, one per iteration: half of Eq. 1's first term, and n times the
+ * per-chunk added time T_fwd(C / n) charged to the other requests. */
+double oracle_waste_chunked_discard(const double *tokens, const double *seconds, int n_pts, double C,
+                                    double C_other, double M, int n_chunks)
+{
+    if (n_chunks < 1) return NAN;
+    double whole = oracle_tfwd(tokens, seconds, n_pts, C);
+    double per_chunk = oracle_tfwd(tokens, seconds, n_pts, C / n_chunks);
+    return whole * C * M / 2.0 + n_chunks * per_chunk * C_other * M;
+}
+
+/* Section 4.2: chunk size = saturation point S minus the running group's size (never negative);
+ * a context of C tokens then takes ceil(C / chunk) iterations. */
+int64_t oracle_chunk_tokens(int64_t S, int64_t running) { return S > running ? S - running : 0; }
+int64_t oracle_chunk_count(int64_t C, int64_t chunk)
+{
+    if (C < 0 || chunk < 1) return -1;
+    return (C + chunk - 1) / chunk;
+}
+
+/* Section 4.2: S is the query-token count past which more tokens lengthen the iteration without
+ * raising throughput.  From a profile of (query tokens q[k], iteration seconds t[k]), q increasing:
+ * the smallest profiled q whose throughput q / t reaches frac (say 0.95) of the best throughput in
+ * the profile (reading: the paper gives no numerical criterion for the knee).  -1 on bad input. */
+int64_t oracle_saturation_point(const double *q, const double *t, int n, double frac)
+{
+    if (n < 1 || !(frac > 0.0) || frac > 1.0) return -1;
+    double best = 0.0;
+    for (int k = 0; k < n; ++k) {
+        if (!(q[k] > 0.0) || !(t[k] > 0.0) || (k > 0 && !(q[k] > q[k - 1]))) return -1;
+        if (q[k] / t[k] > best) best = q[k] / t[k];
+    }
+    for (int k = 0; k < n; ++k)
+        if (q[k] / t[k] >= frac * best) return (int64_t)q[k];
+    return -1;
+}
+
+/*
+ * Section 4.3, scheduling intercepted requests.  Waste_i = min(WastePreserve_i, WasteChunkD_i)
+ * (Eq. 5).  Requests are taken in descending order of that waste (equal wastes: lower index
+ * first) and swapped out until the swap-out budget (tokens) is spent; a request the budget covers
+ * only partly is swapped as far as it goes.  What is left of each request is preserved or
+ * discarded, whichever of its two wastes is smaller (preserve on a tie).
+ * Outputs: swap_tokens[i] tokens of request i to swap out; action[i] for the rest of its context:
+ * 0 = nothing left, 1 = preserve, 2 = discard.  Returns 0, or -1 on bad arguments.
+ */
+int oracle_schedule_intercepted(int n, const double *waste_preserve, const double *waste_chunkd,
+                                const int64_t *ctx_tokens, int64_t budget, int64_t *swap_tokens,
+                                int32_t *action)
+{
+    if (n < 0 || budget < 0) return -1;
+    int *order = (int *)malloc(sizeof(int) * (size_t)(n ? n : 1));
+    if (!order) return -1;
+    for (int i = 0; i < n; ++i) {
+        if (ctx_tokens[i] < 0 || !(waste_preserve[i] >= 0.0) || !(waste_chunkd[i] >= 0.0)) { free(order); return -1; }
+        order[i] = i;
+    }
+    for (int a = 1; a < n; ++a) {                     /* insertion sort: stable, descending waste */
+        int v = order[a];
+        double wv = fmin(waste_preserve[v], waste_chunkd[v]);
+        int b = a - 1;
+        while (b >= 0 && fmin(waste_preserve[order[b]], waste_chunkd[order[b]]) < wv) { order[b + 1] = order[b]; --b; }
+        order[b + 1] = v;
+    }
+    int64_t left = budget;
+    for (int r = 0; r < n; ++r) {
+        int i = order[r];
+        int64_t take = ctx_tokens[i] < left ? ctx_tokens[i] : left;
+        swap_tokens[i] = take;
+        left -= take;
+        if (ctx_tokens[i] - take == 0) action[i] = 0;
+        else action[i] = waste_preserve[i] <= waste_chunkd[i] ? 1 : 2;
+    }
+    free(order);
+    return 0;
 }
 
 int oracle_num_threads(void)

@@ -491,3 +491,96 @@ def test_kv_append_rejects_bad_descriptors_and_shared_slots():
     with pytest.raises(oracle.OracleError):
         oracle.kv_append(pool, ctx, ql, batch.q_start, bt, k_new, v_new)        # slot 0 addressed twice
     assert np.array_equal(pool, before), "a rejected call must not write"
+
+
+# ---------------------------------------------------------------------------------------------
+# GPU-memory-waste model (Eq. 1-5), saturation point, interception schedule
+# ---------------------------------------------------------------------------------------------
+def test_tfwd_is_the_profile_at_its_points_and_linear_between():
+    t = oracle.TfwdTable([100, 200, 400], [0.01, 0.02, 0.05])
+    for x, y in zip([100, 200, 400], [0.01, 0.02, 0.05]):
+        assert oracle.tfwd(t, x) == y
+    assert oracle.tfwd(t, 0) == 0.0
+    assert math.isclose(oracle.tfwd(t, 50), 0.005, rel_tol=1e-15)           # ray through the origin
+    assert math.isclose(oracle.tfwd(t, 150), 0.015, rel_tol=1e-15)
+    assert math.isclose(oracle.tfwd(t, 300), 0.035, rel_tol=1e-15)          # second segment has another slope
+    assert math.isclose(oracle.tfwd(t, 800), 0.05 + 400 * 0.03 / 200, rel_tol=1e-15)   # last slope continues
+    # a profile that IS a line is reproduced everywhere (catches an off-by-one in the segment search)
+    lin = oracle.TfwdTable([10, 70, 300, 1000], [0.02, 0.14, 0.6, 2.0])
+    for x in [0, 3, 10, 11, 69, 70, 71, 299, 301, 999, 5000]:
+        assert math.isclose(oracle.tfwd(lin, x), 0.002 * x, rel_tol=1e-14, abs_tol=1e-18)
+    assert math.isnan(oracle.tfwd(oracle.TfwdTable([10, 10], [1, 2]), 5))    # not increasing
+    assert math.isnan(oracle.tfwd(lin, -1))
+
+
+def test_waste_equations_closed_forms():
+    a, M = 2e-5, 819200.0
+    lin = oracle.TfwdTable([1000.0], [a * 1000.0])                           # T_fwd(x) = a x
+    C, C_other = 1500.0, 90000.0
+    # Eq. 1 with linear T_fwd: a C (C + C_other) M.  Catches a dropped second term.
+    assert math.isclose(oracle.waste_discard(lin, C, C_other, M), a * C * (C + C_other) * M, rel_tol=1e-14)
+    # Eq. 2, Eq. 3 by hand: 3 s x 1500 tokens x M; 2 x 0.25 s x 91500 tokens x M
+    assert oracle.waste_preserve(3.0, 1500.0, M) == 3.0 * 1500.0 * M
+    assert oracle.waste_swap(0.25, 91500.0, M) == 2.0 * 0.25 * 91500.0 * M
+    # Eq. 4: first term is HALF of Eq. 1's; with a linear T_fwd the second term equals Eq. 1's for any n
+    for n in (1, 2, 3, 7):
+        got = oracle.waste_chunked_discard(lin, C, C_other, M, n)
+        assert math.isclose(got, a * C * C * M / 2 + a * C * C_other * M, rel_tol=1e-14), n
+    # with a profile that grows faster than linearly, n T(C/n) <= T(C) (the inequality of Section 4.2)
+    # so Eq. 4 < Eq. 1, strictly, and more chunks never cost more
+    cvx = oracle.TfwdTable([256, 512, 1024, 2048, 4096], [0.010, 0.022, 0.050, 0.120, 0.300])
+    d = oracle.waste_discard(cvx, 4096, C_other, M)
+    prev = None
+    for n in (1, 2, 4, 8, 16):
+        w = oracle.waste_chunked_discard(cvx, 4096, C_other, M, n)
+        assert w < d
+        assert n * oracle.tfwd(cvx, 4096 / n) <= oracle.tfwd(cvx, 4096) * (1 + 1e-15)
+        assert prev is None or w <= prev * (1 + 1e-15)
+        prev = w
+    # n = 1 by hand: T(C) C M / 2 + T(C) C_other M
+    assert math.isclose(oracle.waste_chunked_discard(cvx, 2048, 500.0, 2.0, 1), 0.12 * 2048 * 2 / 2 + 0.12 * 500 * 2,
+                        rel_tol=1e-14)
+    assert math.isnan(oracle.waste_chunked_discard(cvx, 2048, 500.0, 2.0, 0))
+
+
+def test_chunk_size_and_count():
+    assert oracle.chunk_tokens(640, 128) == 512 and oracle.chunk_tokens(100, 128) == 0
+    assert oracle.chunk_count(2048, 512) == 4 and oracle.chunk_count(2049, 512) == 5 and oracle.chunk_count(0, 512) == 0
+    assert oracle.chunk_count(10, 0) == -1
+
+
+def test_saturation_point_of_a_profile_with_a_known_knee():
+    # iteration time max(t0, a q): throughput q / t rises up to q* = t0 / a = 500 and is flat beyond
+    q = np.array([64, 128, 256, 384, 480, 512, 768, 1024, 2048], dtype=np.float64)
+    t = np.maximum(1e-3, 2e-6 * q)
+    assert oracle.saturation_point(q, t, 0.95) == 480                        # 480 / 500 = 0.96 of the plateau
+    assert oracle.saturation_point(q, t, 1.0) == 512
+    assert oracle.saturation_point(q, t, 0.5) == 256
+    # a profile still rising at its end saturates at its last point
+    assert oracle.saturation_point([10, 20, 40], [1.0, 1.0, 1.0], 0.95) == 40
+    assert oracle.saturation_point([10, 10], [1.0, 1.0], 0.95) == -1
+
+
+def test_schedule_intercepted_against_a_python_restatement():
+    rng = np.random.default_rng(31)
+    for _ in range(200):
+        n = int(rng.integers(0, 12))
+        wp = rng.integers(0, 6, size=n).astype(np.float64)                  # small integers: plenty of ties
+        wc = rng.integers(0, 6, size=n).astype(np.float64)
+        ctx = rng.integers(0, 50, size=n).astype(np.int64)
+        budget = int(rng.integers(0, 200))
+        sw, act = oracle.schedule_intercepted(wp, wc, ctx, budget)
+        order = sorted(range(n), key=lambda i: (-min(wp[i], wc[i]), i))
+        left, want_sw = budget, np.zeros(n, dtype=np.int64)
+        for i in order:
+            want_sw[i] = min(int(ctx[i]), left); left -= int(want_sw[i])
+        assert np.array_equal(sw, want_sw)
+        assert sw.sum() == min(budget, int(ctx.sum()))
+        for i in range(n):
+            rest = ctx[i] - sw[i]
+            assert act[i] == (0 if rest == 0 else (1 if wp[i] <= wc[i] else 2))
+    # worked example: wastes min = [5, 1, 2, 9]; budget 120 goes to request 3 (30), then request 0 (90 of 100)
+    sw, act = oracle.schedule_intercepted([5, 1, 9, 9], [6, 3, 2, 20], [100, 50, 70, 30], 120)
+    assert list(sw) == [90, 0, 0, 30] and list(act) == [1, 1, 2, 0]
+    with pytest.raises(oracle.OracleError):
+        oracle.schedule_intercepted([1.0], [float("nan")], [5], 10)
