@@ -41,9 +41,10 @@ def parse_args():
     ap.add_argument("--serial-spans", type=int, default=0)
     ap.add_argument("--row-launch", type=int, default=0)
     ap.add_argument("--row-slots", type=int, default=0)
-    ap.add_argument("--mode", default="hot_path", choices=["hot_path", "swap_pipeline"],
+    ap.add_argument("--mode", default="hot_path", choices=["hot_path", "swap_pipeline", "saturation"],
                     help="hot_path: the step described above (default); swap_pipeline: the layer-pipelined "
-                         "swap to pinned host memory, alone and behind the attention call")
+                         "swap to pinned host memory, alone and behind the attention call; saturation: "
+                         "T_fwd profile of the attention call against query tokens, saturation point, waste model")
     ap.add_argument("--layers", type=int, default=8, help="swap_pipeline: layers (pools) moved per call")
     ap.add_argument("--swap-blocks", type=int, default=512, help="swap_pipeline: blocks per layer per call")
     ap.add_argument("--stages", type=int, default=2, help="swap_pipeline: staging buffers")
@@ -248,17 +249,89 @@ def swap_pipeline_bench(args):
     print(json.dumps(result))
 
 
+def saturation_bench(args):
+    """Section 4.2 on this machine, attention only: time of one layer's attention call for the 13B-shaped
+    decode batch plus a growing number of recomputation query tokens -> T_fwd profile, saturation
+    point S, chunk size, and the waste of Eq. 1 / Eq. 4 for one interception with this profile."""
+    import dataclasses
+    import torch
+    from paper_2402_01869_amd import binding as B
+    from paper_2402_01869_amd import workloads as W
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    base = W.MIXED_13B
+    H, D = base.num_heads, base.head_dim
+    pool_t = torch.empty(W.pool_shape(base.pool_blocks, H, 16, D), dtype=torch.bfloat16, device=dev)
+    W.fill_pool_device_normal(pool_t, base.seed)
+    pool = B.KvPool.from_tensor(pool_t, H, D)
+    stream = torch.cuda.current_stream().cuda_stream
+    sweep = [(0, 0), (1, 64), (1, 128), (1, 256), (1, 512), (2, 512), (3, 512), (4, 512), (6, 512), (8, 512),
+             (12, 512), (16, 512), (32, 512), (64, 512), (128, 512)]
+    q_tokens, seconds, rows = [], [], []
+    for n_span, span_len in sweep:
+        cfg = dataclasses.replace(base, n_span=n_span, span_len=span_len)
+        batch = W.make_batch(cfg, base.seed)
+        desc = B.HostDesc.from_batch(batch, flags=0)
+        q = torch.randn((batch.total_q_rows, H, D), device=dev).to(torch.bfloat16)
+        out = torch.empty_like(q)
+        ws = torch.empty(pool.workspace_bytes(desc), dtype=torch.uint8, device=dev)
+        pool.paged_attn_mixed(desc, q.data_ptr(), out.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+        desc.struct.flags = B.IC_FLAG_TRUSTED
+        for timed in (False, True):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps if timed else args.warmup):
+                pool.paged_attn_mixed(desc, q.data_ptr(), out.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+            torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        q_tokens.append(float(batch.total_q_rows)); seconds.append(dt)
+        rows.append({"spans": n_span, "span_len": span_len, "query_tokens": batch.total_q_rows,
+                     "kv_bytes": batch.kv_bytes(), "ms": round(dt * 1e3, 4),
+                     "tokens_per_s": round(batch.total_q_rows / dt, 1)})
+    S = B.saturation_point(q_tokens, seconds, 0.95)
+    running = base.n_decode
+    chunk = B.chunk_tokens(S, running)
+    # T_fwd for the waste model: ADDED iteration time against recomputed tokens (profile minus the decode-only point)
+    added_tok = [qt - q_tokens[0] for qt in q_tokens[1:]]
+    added_s = [max(sc - seconds[0], 0.0) for sc in seconds[1:]]
+    table = B.TfwdTable(added_tok, added_s)
+    M = float(base.token_bytes)
+    dec = W.make_batch(dataclasses.replace(base, n_span=0), base.seed)
+    C_other = float(dec.ctx_len.astype(np.int64).sum())
+    C = 2560.0                                   # an intercepted request's context (the paper's workloads: 750-2200 tokens mean)
+    n_chunks = B.chunk_count(int(C), chunk) if chunk > 0 else -1
+    w_discard = B.waste_discard(table, C, C_other, M)
+    w_chunk = B.waste_chunked_discard(table, C, C_other, M, max(n_chunks, 1))
+    result = {
+        "metric": "saturation point S of the attention call (query tokens)", "value": S, "unit": "tokens",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(seconds[-1] * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{base.name} decode batch ({base.n_decode} sequences) + k spans of up to 512 rows, "
+                               f"H{H} D{D}; attention call of one layer only"},
+        "profile": rows, "saturation_frac": 0.95, "saturated_within_profile": bool(S < q_tokens[-1]), "running_tokens": running, "chunk_tokens": chunk,
+        "waste_example": {"ctx_tokens": C, "other_tokens": C_other, "token_bytes_one_layer": M,
+                          "n_chunks": n_chunks,
+                          "waste_discard_byte_s": w_discard, "waste_chunked_discard_byte_s": w_chunk,
+                          "chunked_over_discard": round(w_chunk / w_discard, 4) if w_discard > 0 else None,
+                          "preserve_breakeven_s": w_chunk / (C * M),
+                          "note": "T_fwd = added time of ONE layer's attention call against recomputed tokens; a whole "
+                                  "model adds its GEMMs, so S here is an upper bound on the model's"},
+    }
+    print(json.dumps(result))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this hot path runs on ONE GPU (no sharding or collectives are built); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
-    if args.mode == "swap_pipeline":
+    if args.mode != "hot_path":
         sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
         from paper_2402_01869_amd import binding as B
         B.lib()
-        return swap_pipeline_bench(args)
+        return swap_pipeline_bench(args) if args.mode == "swap_pipeline" else saturation_bench(args)
     import torch
     sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
     from paper_2402_01869_amd import binding as B

@@ -259,6 +259,60 @@ int64_t ic_swap_schedule(int64_t total_blocks, int32_t block_size, const int64_t
                          int64_t n_iters, int64_t* out_blocks);
 
 /* ------------------------------------------------------------------------------------------
+ * The scheduler's arithmetic (host only, fp64): the GPU-memory-waste model, chunk sizing, the
+ * saturation point and the interception schedule.  Waste is in byte-seconds when token_bytes is M in
+ * bytes and times are in seconds.
+ *
+ * T_fwd, "a mapping from the number of scheduled tokens in a batch to the execution time of that
+ * iteration" (Section 3.2), comes from profiling: n points (tokens[k], seconds[k]), tokens positive
+ * and strictly increasing.  Between points it is evaluated on straight lines, below the first
+ * point on the line from the origin, beyond the last on the last segment's line.  Functions that
+ * take a table return NaN if it is malformed.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t n;
+  const double* tokens;
+  const double* seconds;
+} ic_tfwd_table;
+
+double ic_tfwd_eval(const ic_tfwd_table* table, double tokens);
+
+/* Eq. 1 (Section 3.2): T_fwd(C) * C * M + T_fwd(C) * C_other * M. */
+double ic_waste_discard(const ic_tfwd_table* table, double ctx_tokens, double other_tokens, double token_bytes);
+/* Eq. 2: T_INT * C * M. */
+double ic_waste_preserve(double t_int_s, double ctx_tokens, double token_bytes);
+/* Eq. 3: 2 * T_swap(C) * C_batch * M (a swap that stalls the batch, out and back in). */
+double ic_waste_swap(double t_swap_s, double batch_tokens, double token_bytes);
+/* Eq. 4 (Section 4.2): T_fwd(C) * C * M / 2 + n * T_fwd(C / n) * C_other * M; NaN if n_chunks < 1. */
+double ic_waste_chunked_discard(const ic_tfwd_table* table, double ctx_tokens, double other_tokens,
+                                double token_bytes, int32_t n_chunks);
+
+/* Section 4.2: chunk size = saturation point S - running group size, never below 0; and the
+ * iterations a context then needs, ceil(C / chunk) (-1 if chunk < 1 or C < 0). */
+int64_t ic_chunk_tokens(int64_t saturation_point, int64_t running_tokens);
+int64_t ic_chunk_count(int64_t ctx_tokens, int64_t chunk_tokens);
+
+/*
+ * Saturation point S (Section 4.2) from a profile of iteration time against query tokens (increasing):
+ * the smallest profiled token count whose throughput tokens / seconds reaches `frac` (0 < frac <= 1,
+ * e.g. 0.95) of the best throughput in the profile.  -1 on bad input.
+ */
+int64_t ic_saturation_point(const double* query_tokens, const double* seconds, int32_t n, double frac);
+
+/*
+ * Scheduling intercepted requests (Section 4.3).  Waste_i = min(waste_preserve[i],
+ * waste_chunked_discard[i]) (Eq. 5); requests are swapped out in descending order of that waste (ties:
+ * lower index first) until swap_out_budget_tokens is spent, the last one possibly in part.
+ * swap_tokens[i] receives the tokens of request i to swap out, action[i] what to do with the rest
+ * of its context: IC_ACT_NONE (nothing left), IC_ACT_PRESERVE or IC_ACT_DISCARD, whichever of its
+ * two wastes is smaller (preserve on a tie).  Wastes must be >= 0 and not NaN (IC_EINVAL).
+ */
+enum { IC_ACT_NONE = 0, IC_ACT_PRESERVE = 1, IC_ACT_DISCARD = 2 };
+int ic_schedule_intercepted(int32_t n, const double* waste_preserve, const double* waste_chunked_discard,
+                            const int64_t* ctx_tokens, int64_t swap_out_budget_tokens, int64_t* swap_tokens,
+                            int32_t* action);
+
+/* ------------------------------------------------------------------------------------------
  * Per-kernel timing with HIP events on the launch stream (for roofline reports).  Between
  * ic_prof_begin and ic_prof_end every kernel the pool launches is bracketed by an event pair.
  * ic_prof_end synchronises the recorded events and returns totals per kernel kind.

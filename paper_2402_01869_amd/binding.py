@@ -30,7 +30,10 @@ EXPORTS = (
     "ic_swapper_staging_bytes", "ic_swapper_create", "ic_swapper_destroy", "kv_swap_out_layers",
     "kv_swap_in_layers", "ic_swapper_wait_layer", "ic_swapper_sync_layer", "ic_swapper_sync",
     "ic_host_alloc", "ic_host_free", "ic_swap_limit_tokens", "ic_swap_schedule", "kv_write_span",
+    "ic_tfwd_eval", "ic_waste_discard", "ic_waste_preserve", "ic_waste_swap", "ic_waste_chunked_discard",
+    "ic_chunk_tokens", "ic_chunk_count", "ic_saturation_point", "ic_schedule_intercepted",
 )
+IC_ACT_NONE, IC_ACT_PRESERVE, IC_ACT_DISCARD = 0, 1, 2
 IC_SWAP_OUT, IC_SWAP_IN = 0, 1
 
 
@@ -69,6 +72,10 @@ class ProfStats(C.Structure):
 
 class SwapperCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("num_layers", "max_blocks", "num_stages", "reserved")]
+
+
+class TfwdTableC(C.Structure):
+    _fields_ = [("n", C.c_int32), ("tokens", C.POINTER(C.c_double)), ("seconds", C.POINTER(C.c_double))]
 
 
 class InferceptError(RuntimeError):
@@ -129,7 +136,19 @@ def lib():
         L.ic_swap_limit_tokens.restype = C.c_int64
         L.ic_swap_schedule.argtypes = [C.c_int64, C.c_int32, i64p, C.c_int64, i64p]
         L.ic_swap_schedule.restype = C.c_int64
-        other = ("ic_strerror", "kv_block_bytes", "paged_attn_mixed_workspace_bytes", "ic_swapper_staging_bytes",
+        dbl, f64p, tp = C.c_double, C.POINTER(C.c_double), C.POINTER(TfwdTableC)
+        L.ic_tfwd_eval.argtypes, L.ic_tfwd_eval.restype = [tp, dbl], dbl
+        L.ic_waste_discard.argtypes, L.ic_waste_discard.restype = [tp, dbl, dbl, dbl], dbl
+        L.ic_waste_preserve.argtypes, L.ic_waste_preserve.restype = [dbl, dbl, dbl], dbl
+        L.ic_waste_swap.argtypes, L.ic_waste_swap.restype = [dbl, dbl, dbl], dbl
+        L.ic_waste_chunked_discard.argtypes = [tp, dbl, dbl, dbl, C.c_int32]
+        L.ic_waste_chunked_discard.restype = dbl
+        L.ic_chunk_tokens.argtypes, L.ic_chunk_tokens.restype = [C.c_int64, C.c_int64], C.c_int64
+        L.ic_chunk_count.argtypes, L.ic_chunk_count.restype = [C.c_int64, C.c_int64], C.c_int64
+        L.ic_saturation_point.argtypes, L.ic_saturation_point.restype = [f64p, f64p, C.c_int32, dbl], C.c_int64
+        L.ic_schedule_intercepted.argtypes = [C.c_int32, f64p, f64p, i64p, C.c_int64, i64p, i32p]
+        other = ("ic_tfwd_eval", "ic_waste_discard", "ic_waste_preserve", "ic_waste_swap", "ic_waste_chunked_discard",
+                 "ic_chunk_tokens", "ic_chunk_count", "ic_saturation_point", "ic_strerror", "kv_block_bytes", "paged_attn_mixed_workspace_bytes", "ic_swapper_staging_bytes",
                  "ic_host_alloc", "ic_swap_limit_tokens", "ic_swap_schedule")
         for name in EXPORTS:
             if name not in other:
@@ -379,3 +398,64 @@ class LayerSwapper:
         rc = lib().ic_swapper_sync(self._h)
         if rc != IC_OK:
             raise InferceptError(rc, "ic_swapper_sync")
+
+
+class TfwdTable:
+    """Profiled T_fwd as (tokens, seconds) points, kept alive next to the C struct."""
+
+    def __init__(self, tokens, seconds):
+        self.tokens = np.ascontiguousarray(tokens, dtype=np.float64)
+        self.seconds = np.ascontiguousarray(seconds, dtype=np.float64)
+        if self.tokens.shape != self.seconds.shape or self.tokens.ndim != 1:
+            raise ValueError("tokens and seconds must be 1-D and of one length")
+        f64p = C.POINTER(C.c_double)
+        self.struct = TfwdTableC(int(self.tokens.shape[0]), self.tokens.ctypes.data_as(f64p),
+                                 self.seconds.ctypes.data_as(f64p))
+
+    def __call__(self, tokens: float) -> float:
+        return float(lib().ic_tfwd_eval(C.byref(self.struct), float(tokens)))
+
+
+def waste_discard(table: TfwdTable, ctx_tokens, other_tokens, token_bytes) -> float:
+    return float(lib().ic_waste_discard(C.byref(table.struct), float(ctx_tokens), float(other_tokens), float(token_bytes)))
+
+
+def waste_preserve(t_int_s, ctx_tokens, token_bytes) -> float:
+    return float(lib().ic_waste_preserve(float(t_int_s), float(ctx_tokens), float(token_bytes)))
+
+
+def waste_swap(t_swap_s, batch_tokens, token_bytes) -> float:
+    return float(lib().ic_waste_swap(float(t_swap_s), float(batch_tokens), float(token_bytes)))
+
+
+def waste_chunked_discard(table: TfwdTable, ctx_tokens, other_tokens, token_bytes, n_chunks: int) -> float:
+    return float(lib().ic_waste_chunked_discard(C.byref(table.struct), float(ctx_tokens), float(other_tokens),
+                                                float(token_bytes), int(n_chunks)))
+
+
+def chunk_tokens(saturation_point: int, running_tokens: int) -> int:
+    return int(lib().ic_chunk_tokens(int(saturation_point), int(running_tokens)))
+
+
+def chunk_count(ctx_tokens: int, chunk: int) -> int:
+    return int(lib().ic_chunk_count(int(ctx_tokens), int(chunk)))
+
+
+def saturation_point(query_tokens, seconds, frac: float = 0.95) -> int:
+    q = np.ascontiguousarray(query_tokens, dtype=np.float64)
+    t = np.ascontiguousarray(seconds, dtype=np.float64)
+    f64p = C.POINTER(C.c_double)
+    return int(lib().ic_saturation_point(q.ctypes.data_as(f64p), t.ctypes.data_as(f64p), int(q.shape[0]), float(frac)))
+
+
+def schedule_intercepted(waste_preserve_, waste_chunkd, ctx_tokens, budget: int):
+    """-> (rc, swap_tokens int64 [n], action int32 [n])."""
+    wp = np.ascontiguousarray(waste_preserve_, dtype=np.float64)
+    wc = np.ascontiguousarray(waste_chunkd, dtype=np.float64)
+    ct = np.ascontiguousarray(ctx_tokens, dtype=np.int64)
+    n = int(ct.shape[0])
+    sw, act = np.zeros(n, dtype=np.int64), np.zeros(n, dtype=np.int32)
+    f64p, i64p = C.POINTER(C.c_double), C.POINTER(C.c_int64)
+    rc = int(lib().ic_schedule_intercepted(n, wp.ctypes.data_as(f64p), wc.ctypes.data_as(f64p), ct.ctypes.data_as(i64p),
+                                           int(budget), sw.ctypes.data_as(i64p), act.ctypes.data_as(C.POINTER(C.c_int32))))
+    return rc, sw, act

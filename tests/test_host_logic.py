@@ -1,6 +1,7 @@
 """CPU-only checks of the C-ABI library: exported symbols, validation and launch planning.
 No compute entry point is called here (no GPU in this tier)."""
 import ctypes as C
+import math
 import os
 import re
 
@@ -233,3 +234,65 @@ def test_kv_write_span_validation_happens_before_any_gpu_work():
     dup = B.HostDesc(ctx, b.q_len, b.q_start, bt, b.scale, b.total_q_rows)
     assert p.kv_write_span(dup, k, v, check=False) == B.IC_EDUP
     p.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# Waste model, chunk sizing, saturation point and interception schedule against the oracle
+# ---------------------------------------------------------------------------------------------
+def _close(a, b):
+    if math.isnan(a) or math.isnan(b):
+        return math.isnan(a) and math.isnan(b)
+    return math.isclose(a, b, rel_tol=1e-13, abs_tol=0.0)
+
+
+def test_waste_model_matches_the_oracle():
+    import oracle
+    rng = np.random.default_rng(41)
+    for _ in range(300):
+        n = int(rng.integers(1, 8))
+        tok = np.cumsum(rng.integers(1, 2000, size=n)).astype(np.float64)
+        sec = np.cumsum(rng.uniform(1e-4, 5e-2, size=n))
+        tb, to = B.TfwdTable(tok, sec), oracle.TfwdTable(tok, sec)
+        xs = list(rng.uniform(0, tok[-1] * 2, size=6)) + list(tok) + [0.0]
+        for x in xs:
+            assert _close(tb(x), oracle.tfwd(to, x)), (tok, sec, x)
+        Cc, Co, M = float(rng.integers(1, 8000)), float(rng.integers(0, 200000)), float(rng.integers(1024, 1 << 21))
+        assert _close(B.waste_discard(tb, Cc, Co, M), oracle.waste_discard(to, Cc, Co, M))
+        for k in (1, 2, 5, 16):
+            assert _close(B.waste_chunked_discard(tb, Cc, Co, M, k), oracle.waste_chunked_discard(to, Cc, Co, M, k))
+        ti = float(rng.uniform(0, 30))
+        assert B.waste_preserve(ti, Cc, M) == oracle.waste_preserve(ti, Cc, M)
+        assert B.waste_swap(ti, Cc + Co, M) == oracle.waste_swap(ti, Cc + Co, M)
+    bad_b, bad_o = B.TfwdTable([5, 5], [1, 2]), oracle.TfwdTable([5, 5], [1, 2])
+    assert math.isnan(bad_b(1.0)) and math.isnan(oracle.tfwd(bad_o, 1.0))
+    assert math.isnan(B.waste_chunked_discard(B.TfwdTable([5], [1]), 10, 10, 1, 0))
+    assert math.isnan(B.TfwdTable([5], [1])(-1.0))
+    for S, r in [(640, 128), (100, 128), (0, 0), (512, 512)]:
+        assert B.chunk_tokens(S, r) == oracle.chunk_tokens(S, r)
+    for Cc, ch in [(2048, 512), (2049, 512), (0, 512), (1, 1), (10, 0), (-1, 5)]:
+        assert B.chunk_count(Cc, ch) == oracle.chunk_count(Cc, ch)
+
+
+def test_saturation_point_and_schedule_match_the_oracle():
+    import oracle
+    rng = np.random.default_rng(42)
+    for _ in range(200):
+        n = int(rng.integers(1, 12))
+        q = np.cumsum(rng.integers(1, 600, size=n)).astype(np.float64)
+        t = np.maximum(rng.uniform(5e-4, 2e-3), rng.uniform(1e-6, 4e-6) * q) * rng.uniform(0.97, 1.03, size=n)
+        for frac in (0.5, 0.9, 0.95, 1.0):
+            assert B.saturation_point(q, t, frac) == oracle.saturation_point(q, t, frac)
+    assert B.saturation_point([10, 10], [1, 1]) == oracle.saturation_point([10, 10], [1, 1]) == -1
+    assert B.saturation_point([10, 20], [1, 1], 1.5) == -1
+    for _ in range(300):
+        n = int(rng.integers(0, 14))
+        wp = rng.integers(0, 5, size=n).astype(np.float64) * rng.choice([1.0, 0.5])
+        wc = rng.integers(0, 5, size=n).astype(np.float64)
+        ctx = rng.integers(0, 80, size=n).astype(np.int64)
+        budget = int(rng.integers(0, 300))
+        rc, sw, act = B.schedule_intercepted(wp, wc, ctx, budget)
+        osw, oact = oracle.schedule_intercepted(wp, wc, ctx, budget)
+        assert rc == B.IC_OK and np.array_equal(sw, osw) and np.array_equal(act, oact)
+    assert B.schedule_intercepted([1.0], [float("nan")], [5], 10)[0] == B.IC_EINVAL
+    assert B.schedule_intercepted([1.0], [1.0], [-5], 10)[0] == B.IC_EINVAL
+    assert B.schedule_intercepted([1.0], [1.0], [5], -1)[0] == B.IC_EINVAL
