@@ -32,11 +32,11 @@ def lib():
         i32p, u16p, u8p, f64p = (C.POINTER(C.c_int32), C.POINTER(C.c_uint16),
                                  C.POINTER(C.c_uint8), C.POINTER(C.c_double))
         _lib.oracle_paged_attn_items.argtypes = [
-            u16p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p, i32p, C.c_int,
+            u16p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p, i32p, C.c_int,
             u16p, C.c_double, C.c_int64, i32p, i32p, f64p]
         _lib.oracle_paged_attn_items.restype = C.c_int
         _lib.oracle_paged_attn.argtypes = [
-            u16p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p, i32p, C.c_int,
+            u16p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p, i32p, C.c_int,
             u16p, C.c_double, f64p]
         _lib.oracle_paged_attn.restype = C.c_int
         _lib.oracle_pack_blocks.argtypes = [u8p, C.c_int64, C.c_int64, i32p, C.c_int64, u8p]
@@ -105,17 +105,18 @@ def paged_attn_items(pool_bits, ctx_len, q_len, q_start, block_tables, q_bits, s
     [num_seqs][max_blocks] (unused entries may hold anything).
     """
     pool_bits = _c(pool_bits, np.uint16)
-    nblk, two, H, B, D = pool_bits.shape
+    nblk, two, Hkv, B, D = pool_bits.shape
     assert two == 2
     ctx_len, q_len, q_start = _c(ctx_len, np.int32), _c(q_len, np.int32), _c(q_start, np.int32)
     block_tables = _c(block_tables, np.int32)
     q_bits = _c(q_bits, np.uint16)
-    assert q_bits.ndim == 3 and q_bits.shape[1:] == (H, D)
+    assert q_bits.ndim == 3 and q_bits.shape[2] == D
+    H = int(q_bits.shape[1])          # query heads; the pool holds Hkv <= H key/value heads
     item_seq, item_row = _c(item_seq, np.int32), _c(item_row, np.int32)
     n = item_seq.shape[0]
     out = np.empty((n, H, D), dtype=np.float64)
     rc = lib().oracle_paged_attn_items(
-        _p(pool_bits, C.c_uint16), nblk, B, H, D, ctx_len.shape[0], _p(ctx_len, C.c_int32),
+        _p(pool_bits, C.c_uint16), nblk, B, H, Hkv, D, ctx_len.shape[0], _p(ctx_len, C.c_int32),
         _p(q_len, C.c_int32), _p(q_start, C.c_int32), _p(block_tables, C.c_int32),
         block_tables.shape[1], _p(q_bits, C.c_uint16), float(scale), n,
         _p(item_seq, C.c_int32), _p(item_row, C.c_int32), _p(out, C.c_double))
@@ -127,15 +128,16 @@ def paged_attn(pool_bits, ctx_len, q_len, q_start, block_tables, q_bits, scale,
                total_q_rows: Optional[int] = None) -> np.ndarray:
     """Attention for every row of the batch -> fp64 [total_q_rows][H][D]."""
     pool_bits = _c(pool_bits, np.uint16)
-    nblk, two, H, B, D = pool_bits.shape
+    nblk, two, Hkv, B, D = pool_bits.shape
     assert two == 2
     ctx_len, q_len, q_start = _c(ctx_len, np.int32), _c(q_len, np.int32), _c(q_start, np.int32)
     block_tables = _c(block_tables, np.int32)
     q_bits = _c(q_bits, np.uint16)
+    H = int(q_bits.shape[1])
     rows = int(q_bits.shape[0]) if total_q_rows is None else int(total_q_rows)
     out = np.full((rows, H, D), np.nan, dtype=np.float64)
     rc = lib().oracle_paged_attn(
-        _p(pool_bits, C.c_uint16), nblk, B, H, D, ctx_len.shape[0], _p(ctx_len, C.c_int32),
+        _p(pool_bits, C.c_uint16), nblk, B, H, Hkv, D, ctx_len.shape[0], _p(ctx_len, C.c_int32),
         _p(q_len, C.c_int32), _p(q_start, C.c_int32), _p(block_tables, C.c_int32),
         block_tables.shape[1], _p(q_bits, C.c_uint16), float(scale), _p(out, C.c_double))
     _check(rc)

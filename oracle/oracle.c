@@ -103,15 +103,21 @@ static int attend_one(const uint16_t *pool, int H, int B, int D, const int32_t *
 
 /*
  * Attention for a list of (sequence, row-in-span) items; out is [n_items][H][D] fp64.
+ * H query heads over Hkv key/value heads (the pool holds Hkv heads): Hkv = H is multi-head
+ * attention; with grouped-query attention (the paper's largest model, Section 5) query head h
+ * reads K/V head h / (H / Hkv), i.e. consecutive query heads share a K/V head (reading: the paper
+ * does not print the mapping; this is the grouping of the model family it evaluates).
  * Returns 0 on success, -1 on allocation failure, -2 on an invalid descriptor.
  */
-int oracle_paged_attn_items(const uint16_t *pool, int64_t num_blocks, int B, int H, int D,
+int oracle_paged_attn_items(const uint16_t *pool, int64_t num_blocks, int B, int H, int Hkv, int D,
                             int num_seqs, const int32_t *ctx_len, const int32_t *q_len,
                             const int32_t *q_start, const int32_t *block_tables,
                             int max_blocks_per_seq, const uint16_t *q, double scale,
                             int64_t n_items, const int32_t *item_seq, const int32_t *item_row,
                             double *out)
 {
+    if (Hkv < 1 || H < Hkv || H % Hkv != 0) return -2;
+    const int group = H / Hkv;   /* query heads that share one K/V head */
     for (int64_t it = 0; it < n_items; ++it) {
         int s = item_seq[it];
         if (s < 0 || s >= num_seqs) return -2;
@@ -136,7 +142,7 @@ int oracle_paged_attn_items(const uint16_t *pool, int64_t num_blocks, int B, int
         const int32_t *table = block_tables + (int64_t)s * max_blocks_per_seq;
         const uint16_t *qrow = q + (((int64_t)q_start[s] + i) * H + head) * (int64_t)D;
         double *o = out + (it * H + head) * (int64_t)D;
-        if (attend_one(pool, H, B, D, table, head, p, qrow, scale, o) != 0) {
+        if (attend_one(pool, Hkv, B, D, table, head / group, p, qrow, scale, o) != 0) {
 #pragma omp atomic write
             failed = 1;
         }
@@ -145,7 +151,7 @@ int oracle_paged_attn_items(const uint16_t *pool, int64_t num_blocks, int B, int
 }
 
 /* Every row of every sequence; out is [total_q_rows][H][D] fp64, indexed by q_start[s] + i. */
-int oracle_paged_attn(const uint16_t *pool, int64_t num_blocks, int B, int H, int D, int num_seqs,
+int oracle_paged_attn(const uint16_t *pool, int64_t num_blocks, int B, int H, int Hkv, int D, int num_seqs,
                       const int32_t *ctx_len, const int32_t *q_len, const int32_t *q_start,
                       const int32_t *block_tables, int max_blocks_per_seq, const uint16_t *q,
                       double scale, double *out)
@@ -165,7 +171,7 @@ int oracle_paged_attn(const uint16_t *pool, int64_t num_blocks, int B, int H, in
         for (int i = 0; i < q_len[s]; ++i) {
             iseq[n] = s; irow[n] = i; dst[n] = (int64_t)q_start[s] + i; ++n;
         }
-    int rc = oracle_paged_attn_items(pool, num_blocks, B, H, D, num_seqs, ctx_len, q_len, q_start,
+    int rc = oracle_paged_attn_items(pool, num_blocks, B, H, Hkv, D, num_seqs, ctx_len, q_len, q_start,
                                      block_tables, max_blocks_per_seq, q, scale, n_items, iseq, irow, tmp);
     if (rc == 0)
         for (int64_t k = 0; k < n_items; ++k)

@@ -584,3 +584,43 @@ def test_schedule_intercepted_against_a_python_restatement():
     assert list(sw) == [90, 0, 0, 30] and list(act) == [1, 1, 2, 0]
     with pytest.raises(oracle.OracleError):
         oracle.schedule_intercepted([1.0], [float("nan")], [5], 10)
+
+
+# ---------------------------------------------------------------------------------------------
+# Grouped-query attention: H query heads over Hkv key/value heads
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("H,Hkv", [(8, 2), (8, 8), (6, 1), (64, 8)])
+def test_gqa_equals_mha_on_replicated_kv_heads(H, Hkv):
+    # Replicating every K/V head G times turns the grouped problem into the multi-head one the pins above
+    # cover; outputs must agree bit for bit.  Catches h % G instead of h / G, and a pool stride of H.
+    rng = np.random.default_rng(H * 100 + Hkv)
+    D, nb, G = 16, 24, H // Hkv
+    batch = W.assemble_batch(Hkv, D, B, nb, [37, 16, 50], [1, 16, 9], rng)
+    pool = W.randn_bf16(W.pool_shape(nb, Hkv, B, D), rng)
+    q = W.randn_bf16((batch.total_q_rows, H, D), rng)
+    got = oracle.paged_attn(pool, batch.ctx_len, batch.q_len, batch.q_start, batch.block_tables, q, 0.3)
+    wide = np.repeat(pool, G, axis=2)                                        # kv head j -> query heads jG..jG+G-1
+    want = oracle.paged_attn(wide, batch.ctx_len, batch.q_len, batch.q_start, batch.block_tables, q, 0.3)
+    assert got.shape == (batch.total_q_rows, H, D)
+    assert np.array_equal(got, want)
+
+
+def test_gqa_matches_dense_numpy_with_explicit_head_map():
+    rng = np.random.default_rng(55)
+    H, Hkv, D, ctx, n = 6, 2, 8, 45, 12
+    K = W.randn_bf16((ctx, Hkv, D), rng); V = W.randn_bf16((ctx, Hkv, D), rng); q = W.randn_bf16((n, H, D), rng)
+    table = rng.permutation(6)[:3].astype(np.int32)
+    pool = paged_pool_from_dense(K, V, table, B, 6)
+    out = oracle.paged_attn(pool, [ctx], [n], [0], table[None, :], q, 0.25)
+    head_map = [0, 0, 0, 1, 1, 1]
+    Kw, Vw = W.bf16_bits_to_f64(K)[:, head_map], W.bf16_bits_to_f64(V)[:, head_map]
+    want = dense_causal_attention(W.bf16_bits_to_f64(q), Kw, Vw, 0.25, ctx - n)
+    assert np.abs(out - want).max() < 1e-12
+
+
+def test_gqa_rejects_heads_that_do_not_divide():
+    rng = np.random.default_rng(56)
+    pool = W.randn_bf16(W.pool_shape(4, 3, B, 8), rng)
+    q = W.randn_bf16((1, 4, 8), rng)
+    with pytest.raises(oracle.OracleError):
+        oracle.paged_attn(pool, [5], [1], [0], np.zeros((1, 1), dtype=np.int32), q, 1.0)
