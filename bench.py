@@ -33,7 +33,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="mixed_13b", choices=["mixed_13b", "gptj_decode", "long_ctx", "tiny"])
+    ap.add_argument("--workload", default="mixed_13b", choices=["mixed_13b", "gptj_decode", "long_ctx", "tiny", "gqa_70b"])
     ap.add_argument("--decode-part", type=int, default=0)
     ap.add_argument("--span-part", type=int, default=0)
     ap.add_argument("--span-kernel", type=int, default=0)
@@ -341,7 +341,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    acfg = {"mixed_13b": W.MIXED_13B, "gptj_decode": W.GPTJ_DECODE, "long_ctx": W.LONG_CTX, "tiny": W.TINY}[args.workload]
+    acfg = {"mixed_13b": W.MIXED_13B, "gptj_decode": W.GPTJ_DECODE, "long_ctx": W.LONG_CTX, "tiny": W.TINY,
+            "gqa_70b": W.GQA_70B}[args.workload]
     scfg = W.TINY_SWAP if args.workload == "tiny" else W.KV_SWAP
     if args.decode_only:
         import dataclasses
@@ -349,9 +350,9 @@ def main():
     H, D = acfg.num_heads, acfg.head_dim
 
     # ---- attention inputs: one pool, two batches (different tables) alternated between steps
-    pool_t = torch.empty(W.pool_shape(acfg.pool_blocks, H, 16, D), dtype=torch.bfloat16, device=dev)
+    pool_t = torch.empty(W.pool_shape(acfg.pool_blocks, acfg.kv_heads, 16, D), dtype=torch.bfloat16, device=dev)
     W.fill_pool_device_normal(pool_t, acfg.seed)
-    pool = B.KvPool.from_tensor(pool_t, H, D)
+    pool = B.KvPool.from_tensor(pool_t, H, D, num_kv_heads=acfg.kv_heads)
     pool.set_tuning(args.decode_part, args.span_part, args.span_kernel, args.row_variant, args.serial_spans, args.row_launch, args.row_slots)
     batches = [W.make_batch(acfg, acfg.seed), W.make_batch(acfg, acfg.seed + 1000)]
     descs, qs, outs = [], [], []
@@ -469,8 +470,8 @@ def main():
     # attention outputs above were already taken.
     append = None
     if not args.no_append:
-        kn = [torch.randn((b.total_q_rows, H, D), device=dev).to(torch.bfloat16) for b in batches]
-        vn = [torch.randn((b.total_q_rows, H, D), device=dev).to(torch.bfloat16) for b in batches]
+        kn = [torch.randn((b.total_q_rows, acfg.kv_heads, D), device=dev).to(torch.bfloat16) for b in batches]
+        vn = [torch.randn((b.total_q_rows, acfg.kv_heads, D), device=dev).to(torch.bfloat16) for b in batches]
         n_ap = max(10, args.steps // 2)
         for timed in (False, True):
             if timed:
@@ -481,7 +482,7 @@ def main():
             torch.cuda.synchronize()
         ap = pool.prof_end()["append"]
         ap_ms = ap["total_ms"] / ap["launches"]
-        ap_bytes = float(np.mean([2.0 * 2 * b.total_q_rows * H * D * 2 for b in batches]))   # K and V, read + write
+        ap_bytes = float(np.mean([2.0 * 2 * b.total_q_rows * acfg.kv_heads * D * 2 for b in batches]))   # K and V, read + write
         append = {"rows": int(np.mean([b.total_q_rows for b in batches])), "moved_bytes": ap_bytes,
                   "avg_ms": round(ap_ms, 5), "min_ms": round(ap["min_ms"], 5),
                   "GBps": round(ap_bytes / (ap_ms * 1e-3) / 1e9, 1),

@@ -36,7 +36,7 @@ enum {
   IC_ESIZE = -4,        /* a caller buffer (pool, staging, workspace, table) is too small */
   IC_EALIGN = -5,       /* a device pointer is not 16-byte aligned                      */
   IC_EDUP = -6,         /* duplicate destination id in kv_unpack_blocks                 */
-  IC_EUNSUPPORTED = -7, /* dtype, layout, head_dim, GQA ... not built                   */
+  IC_EUNSUPPORTED = -7, /* dtype, layout, head_dim, block size ... not built            */
   IC_EOVERLAP = -8,     /* query-row ranges of two sequences overlap or leave [0,total) */
   IC_EHIP = -9,         /* the HIP runtime reported an error                            */
   IC_ENOMEM = -10       /* host allocation failed                                       */
@@ -49,7 +49,7 @@ const char* ic_strerror(int code);
  * The block pool (paper Section 3.1: the KV cache is virtual memory whose pages are physical
  * blocks anywhere in GPU memory; Section 3.2 calls the per-token footprint M).
  *
- * layout 0:  pool[block][kv][head][slot][dim], kv = 0 for K and 1 for V, bf16.
+ * layout 0:  pool[block][kv][kv_head][slot][dim], kv = 0 for K and 1 for V, bf16.
  *   One block = block_size tokens of ONE layer = block_size * M bytes, contiguous, so a swap
  *   moves whole blocks; inside it each (kv, head) tile of block_size x head_dim is contiguous,
  *   so attention reads it with full-width coalesced loads.
@@ -58,7 +58,9 @@ typedef struct {
   int32_t num_blocks;   /* >= 1                                                          */
   int32_t block_size;   /* tokens per block; 16 is the only size built                   */
   int32_t num_heads;    /* query heads                                                   */
-  int32_t num_kv_heads; /* must equal num_heads (multi-head attention)                   */
+  int32_t num_kv_heads; /* K/V heads in the pool; divides num_heads.  Equal: multi-head attention;
+                           fewer: grouped-query attention, query head h reads K/V head
+                           h / (num_heads / num_kv_heads)                                */
   int32_t head_dim;     /* 64, 128 or 256                                                */
   int32_t dtype;        /* 0 = bf16                                                      */
   int32_t layout;       /* 0 = the layout above                                          */

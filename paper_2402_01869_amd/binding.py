@@ -213,11 +213,13 @@ class KvPool:
             raise InferceptError(rc, "kv_pool_init")
 
     @classmethod
-    def from_tensor(cls, pool_t, num_heads, head_dim, block_size=16):
-        """pool_t: a contiguous torch device tensor holding [blocks][2][H][B][D] bf16."""
+    def from_tensor(cls, pool_t, num_heads, head_dim, block_size=16, num_kv_heads=None):
+        """pool_t: a contiguous torch device tensor holding [blocks][2][Hkv][B][D] bf16 (Hkv = num_kv_heads,
+        num_heads if not given)."""
         nbytes = pool_t.numel() * pool_t.element_size()
-        bb = block_size * 2 * num_heads * head_dim * 2
-        obj = cls(make_cfg(nbytes // bb, num_heads, head_dim, block_size), pool_t.data_ptr(), nbytes)
+        hkv = num_heads if num_kv_heads is None else num_kv_heads
+        bb = block_size * 2 * hkv * head_dim * 2
+        obj = cls(make_cfg(nbytes // bb, num_heads, head_dim, block_size, hkv), pool_t.data_ptr(), nbytes)
         obj._keep = pool_t
         return obj
 

@@ -10,12 +10,12 @@ using namespace tilep;
 template <int D>
 __global__ __launch_bounds__(TW<D>::kThreads, (D <= 128 ? 2 : 1)) void tile_attn_kernel(AttnParams p) {
   __shared__ __attribute__((aligned(16))) uint16_t lds[tile_lds_bytes<D>() / 2];
-  const int H = p.num_heads;
+  const int n_th = p.num_heads >> p.tile_g_shift;  // head groups, each served by one workgroup per item
   const uint32_t wg = blockIdx.x;
-  const int item_idx = wg / H;
-  const int head = wg - item_idx * H;
+  const int item_idx = wg / n_th;
+  const int th = wg - item_idx * n_th;
   const TileItem it = p.tile_items[item_idx];
-  tile_body<D>(p, it, head, lds);
+  tile_body<D>(p, it, th, lds);
 }
 
 // Persistent launch of the same body, for running beside the row kernel: `slots` workgroups (one
@@ -24,24 +24,35 @@ __global__ __launch_bounds__(TW<D>::kThreads, (D <= 128 ? 2 : 1)) void tile_attn
 // (L2 domains) by block index, so XCD x = index % 8 owns the tile items of the heads h = x (mod 8),
 // in head-major order: the query tiles of one (sequence, head), which read the same keys, run on
 // one L2 at the same time, and each span's keys are fetched from HBM about once.
+// Register budget: at most 216 per lane for head_dim <= 128 (checked by the test-suite from the
+// compiler's resource report).  Two waves of this kernel (432) and one of the slim row kernel (80)
+// fill the 512 of a SIMD exactly, which is what lets one workgroup of each share a CU.
 template <int D>
 __global__ __launch_bounds__(TW<D>::kThreads, (D <= 128 ? 2 : 1)) void tile_persist_kernel(AttnParams p) {
   __shared__ __attribute__((aligned(16))) uint16_t lds[tile_lds_bytes<D>() / 2];
   __shared__ int s_next;
-  const int H = p.num_heads;
+  const int H = p.num_heads >> p.tile_g_shift;               // head groups
+  const bool per_xcd = H >= 8;   // with fewer head groups than XCDs, one shared queue (counters[9]) instead
   const uint32_t x = blockIdx.x & 7u;
-  const uint32_t heads_x = (uint32_t)(H - (int)x + 7) / 8u;  // heads congruent to x mod 8
-  const uint32_t n_t = (uint32_t)p.n_tile_items * heads_x;
+  const uint32_t heads_x = (uint32_t)(H - (int)x + 7) / 8u;  // head groups congruent to x mod 8
+  const uint32_t n_t = (uint32_t)p.n_tile_items * (per_xcd ? heads_x : (uint32_t)H);
   for (;;) {
-    if (threadIdx.x == 0) s_next = atomicAdd(&p.counters[x], 1);
+    if (threadIdx.x == 0) s_next = atomicAdd(&p.counters[per_xcd ? x : 9u], 1);
     __syncthreads();
     const uint32_t idx = (uint32_t)s_next;
     __syncthreads();  // s_next is rewritten at the top of the next round
     if (idx >= n_t) break;
-    const uint32_t hsel = idx / (uint32_t)p.n_tile_items;
-    const uint32_t item = idx - hsel * (uint32_t)p.n_tile_items;
+    uint32_t item, th;
+    if (per_xcd) {
+      const uint32_t hsel = idx / (uint32_t)p.n_tile_items;
+      item = idx - hsel * (uint32_t)p.n_tile_items;
+      th = x + 8u * hsel;
+    } else {
+      item = idx / (uint32_t)H;
+      th = idx - item * (uint32_t)H;
+    }
     const TileItem it = p.tile_items[item];
-    tile_body<D>(p, it, (int)(x + 8u * hsel), lds);
+    tile_body<D>(p, it, (int)th, lds);
     __syncthreads();  // the body leaves LDS in use until every wave is through
   }
 }
@@ -50,7 +61,7 @@ __global__ __launch_bounds__(TW<D>::kThreads, (D <= 128 ? 2 : 1)) void tile_pers
 
 hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st) {
   if (p.n_tile_items <= 0) return hipSuccess;
-  const uint64_t grid = (uint64_t)p.n_tile_items * p.num_heads;
+  const uint64_t grid = (uint64_t)p.n_tile_items * (uint64_t)(p.num_heads >> p.tile_g_shift);
   if (grid > 0x7fffffffull) return hipErrorInvalidValue;
   const dim3 g((uint32_t)grid);
   switch (head_dim) {

@@ -63,7 +63,7 @@ int check_cfg(const ic_pool_cfg* c) {
     return IC_EINVAL;
   if (c->dtype != 0 || c->layout != 0) return IC_EUNSUPPORTED;
   if (c->block_size != kBlockSize) return IC_EUNSUPPORTED;
-  if (c->num_kv_heads != c->num_heads) return IC_EUNSUPPORTED;
+  if (c->num_kv_heads > c->num_heads || c->num_heads % c->num_kv_heads != 0) return IC_EINVAL;
   if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return IC_EUNSUPPORTED;
   if (c->num_heads > 4096) return IC_EINVAL;
   return IC_OK;
@@ -128,8 +128,10 @@ int check_ids(const ic_pool_cfg& cfg, const int32_t* ids, int32_t n, bool distin
 // ---------------------------------------------------------------------------------------
 struct PlanSizes {
   ic_plan_info info;
-  int row_part, span_part, tile_rows;
+  int row_part, span_part, tile_rows;  // tile_rows: QUERY rows per tile item
+  int tile_g_shift;                    // log2 of the query heads one tile workgroup serves
   bool spans_as_rows;
+  bool decode_as_tiles;                // grouped-query pools: the heads of a group share the keys on the MFMA path
   size_t off_ctr, off_bt_off, off_bt_flat, off_row, off_tile, off_merge, image_bytes;
   size_t off_part_o, off_part_ml, total_bytes;
 };
@@ -138,7 +140,14 @@ int round64(int x) { return (x + 63) / 64 * 64; }
 
 void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   std::memset(&ps, 0, sizeof ps);
-  const int kTileRows = tile_rows(pool->cfg.head_dim);
+  // Grouped-query attention: the G = H / Hkv query heads of a group read the same keys.  When G is a
+  // power of two up to 32, a tile workgroup takes all of them (G rows per query row), so keys are
+  // staged once per group, and decode rows (G rows of one query token) go to the MFMA path too.
+  const int G = pool->cfg.num_heads / pool->cfg.num_kv_heads;
+  ps.tile_g_shift = 0;
+  if (G >= 2 && G <= 32 && (G & (G - 1)) == 0)
+    while ((1 << ps.tile_g_shift) < G) ++ps.tile_g_shift;
+  const int kTileRows = tile_rows(pool->cfg.head_dim) >> ps.tile_g_shift;
   ps.tile_rows = kTileRows;
   const ic_tuning& t = pool->tune;
   ps.row_part = t.decode_part_tokens > 0 ? round64(t.decode_part_tokens)
@@ -146,11 +155,12 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   ps.row_part = std::min(ps.row_part, kMaxRowPart);
   ps.span_part = t.span_part_tokens > 0 ? round64(t.span_part_tokens) : kDefaultSpanPart;
   ps.spans_as_rows = (t.span_kernel == 1);  // default: MFMA tiles
+  ps.decode_as_tiles = ps.tile_g_shift > 0 && t.span_kernel != 1;
   ic_plan_info& in = ps.info;
   for (int s = 0; s < d->num_seqs; ++s) {
     const int c = d->ctx_len[s], n = d->q_len[s];
     in.table_entries += (c + kBlockSize - 1) / kBlockSize;
-    if (n == 1 || ps.spans_as_rows) {
+    if (n == 1 ? !ps.decode_as_tiles : ps.spans_as_rows) {
       if (n == 1) in.decode_rows += 1; else in.span_rows += n;
       for (int i = 0; i < n; ++i) {
         const int klen = c - n + i + 1;
@@ -159,11 +169,12 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
         if (parts > 1) { in.partial_slots += parts; in.merge_rows += 1; }
       }
     } else {
-      in.span_rows += n;
+      if (n == 1) in.decode_rows += 1; else in.span_rows += n;
+      const int part = n == 1 ? ps.row_part : ps.span_part;
       for (int r0 = 0; r0 < n; r0 += kTileRows) {
         const int nr = std::min(kTileRows, n - r0);
         const int klen = c - n + r0 + nr;  // keys visible to the tile's last row
-        const int parts = (klen + ps.span_part - 1) / ps.span_part;
+        const int parts = (klen + part - 1) / part;
         in.tile_items += parts;
         if (parts > 1) { in.partial_slots += parts * nr; in.merge_rows += nr; }
       }
@@ -200,7 +211,7 @@ void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
     std::memcpy(bt_flat + nbt, d->block_tables + (int64_t)s * d->max_blocks_per_seq,
                 sizeof(int32_t) * (size_t)nb);
     nbt += nb;
-    if (n == 1 || ps.spans_as_rows) {
+    if (n == 1 ? !ps.decode_as_tiles : ps.spans_as_rows) {
       for (int i = 0; i < n; ++i) {
         const int klen = c - n + i + 1;
         const int parts = (klen + ps.row_part - 1) / ps.row_part;
@@ -220,13 +231,14 @@ void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
       // slots first (per tile: rows x partitions), then items ordered partition-major so that the
       // query tiles which read the same keys are dispatched next to each other
       const int ntile = (n + kTileRows - 1) / kTileRows;
+      const int part = n == 1 ? ps.row_part : ps.span_part;
       int max_parts = 0;
       std::vector<int> tile_slot0((size_t)ntile, -1), tile_parts((size_t)ntile, 0);
       for (int ti = 0; ti < ntile; ++ti) {
         const int r0 = ti * kTileRows;
         const int nr = std::min(kTileRows, n - r0);
         const int klen = c - n + r0 + nr;
-        const int parts = (klen + ps.span_part - 1) / ps.span_part;
+        const int parts = (klen + part - 1) / part;
         tile_parts[ti] = parts;
         max_parts = std::max(max_parts, parts);
         if (parts > 1) {
@@ -248,8 +260,8 @@ void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
           it.qrow0 = d->q_start[s] + r0;
           it.n_rows = nr;
           it.pos0 = pos0;
-          it.k_begin = k * ps.span_part;
-          it.k_end = std::min(klen, (k + 1) * ps.span_part);
+          it.k_begin = k * part;
+          it.k_end = std::min(klen, (k + 1) * part);
           it.slot0 = tile_parts[ti] > 1 ? tile_slot0[ti] + k : -1;
           it.nparts = tile_parts[ti];
         }
@@ -451,6 +463,9 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
   p.part_o = (float*)(ws + ps.off_part_o);
   p.part_ml = (float*)(ws + ps.off_part_ml);
   p.num_heads = pool->cfg.num_heads;
+  p.num_kv_heads = pool->cfg.num_kv_heads;
+  p.group = pool->cfg.num_heads / pool->cfg.num_kv_heads;
+  p.tile_g_shift = ps.tile_g_shift;
   p.n_row_items = ps.info.row_items;
   p.n_tile_items = ps.info.tile_items;
   p.n_merge_items = ps.info.merge_rows;

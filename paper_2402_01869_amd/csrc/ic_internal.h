@@ -36,8 +36,9 @@ struct RowItem {
   int32_t pad[3];
 };
 
-// One work item of the MFMA tile kernel: up to tile_rows(D) consecutive rows of one span against keys
-// [k_begin, k_end) (k_end is a bound for the LAST row; earlier rows see fewer keys).
+// One work item of the MFMA tile kernel: up to tile_rows(D) >> tile_g_shift consecutive query rows of one
+// sequence, for the 1 << tile_g_shift query heads that share a K/V head, against keys [k_begin, k_end)
+// (k_end is a bound for the LAST row; earlier rows see fewer keys).
 struct TileItem {
   int32_t seq;
   int32_t qrow0;    // first row of the tile in packed q / out
@@ -68,7 +69,11 @@ struct AttnParams {
   const MergeItem* merge_items;
   float* part_o;           // [slots][H][D] unnormalised partial outputs
   float* part_ml;          // [slots][H][2] (running max in log2 units, normaliser)
-  int32_t num_heads;
+  int32_t num_heads;       // query heads H
+  int32_t num_kv_heads;    // key/value heads in the pool; query head h reads K/V head h / group
+  int32_t group;           // H / num_kv_heads
+  int32_t tile_g_shift;    // log2 of the query heads one tile workgroup serves (they share K/V): a tile's
+                           // row r is query row r >> shift, head (first head of the workgroup) + (r & mask)
   int32_t n_row_items;
   int32_t n_tile_items;
   int32_t n_merge_items;

@@ -154,6 +154,8 @@ __device__ __forceinline__ void row_body(const AttnParams& p, const RowItem& it,
   constexpr int STAGES = PF + 1;  // register buffers
 
   const int H = p.num_heads;
+  const int Hk = p.num_kv_heads;
+  const int kvh = head / p.group;   // the K/V head this query head reads
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
@@ -178,7 +180,7 @@ __device__ __forceinline__ void row_body(const AttnParams& p, const RowItem& it,
   Tile<D> buf[STAGES];
 #pragma unroll
   for (int s = 0; s < PF; ++s)
-    if (s < nb_w) load_tile<D, NT>(buf[s], pool, __builtin_amdgcn_readlane(my_id, s), head, H, lane);
+    if (s < nb_w) load_tile<D, NT>(buf[s], pool, __builtin_amdgcn_readlane(my_id, s), kvh, Hk, lane);
 
   for (int it0 = 0; it0 < nb_w; it0 += STAGES) {
 #pragma unroll
@@ -186,8 +188,8 @@ __device__ __forceinline__ void row_body(const AttnParams& p, const RowItem& it,
       const int i = it0 + s;
       if (i < nb_w) {
         if (i + PF < nb_w)
-          load_tile<D, NT>(buf[(s + PF) % STAGES], pool, __builtin_amdgcn_readlane(my_id, i + PF), head,
-                       H, lane);
+          load_tile<D, NT>(buf[(s + PF) % STAGES], pool, __builtin_amdgcn_readlane(my_id, i + PF), kvh,
+                       Hk, lane);
         const int tok0 = k_begin + (w + kRowWaves * i) * kBlockSize;
         const int n_valid = k_end - tok0;
         if (n_valid >= kBlockSize)

@@ -186,8 +186,12 @@ __device__ __forceinline__ void wave_step(const uint16_t* ks, const uint16_t* vs
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[tt][i], sc, -m_new));
-      psum += pv;
-      pb[2 * tt + i / 8][i % 8] = (__bf16)pv;
+      // The normaliser sums the weights as the matrix core will see them (rounded to bf16): the
+      // output stays an exact convex combination of the values, and a row dominated by one key
+      // (short contexts) does not inherit the 2^-9 relative rounding error of its weight.
+      const __bf16 pr = (__bf16)pv;
+      psum += (float)pr;
+      pb[2 * tt + i / 8][i % 8] = pr;
     }
   l = l * alpha + psum;
   if (__builtin_amdgcn_ballot_w64(grew) != 0) {  // rescale only when some row's maximum moved
@@ -228,13 +232,22 @@ constexpr int tile_lds_bytes() {
   return 2 * tile_buf_elems<D>() * 2;  // two buffers of bf16
 }
 
-// One TileItem x one head, executed by a workgroup of tile_rows(D) / 32 waves.
+// One TileItem x one group of (1 << p.tile_g_shift) query heads that share a K/V head, executed by a
+// workgroup of tile_rows(D) / 32 waves.  th = index of the head group: its heads are
+// th << shift .. ((th + 1) << shift) - 1.  Row r of the tile is query row r >> shift of the item for
+// head (th << shift) + (r & mask): with multi-head attention (shift 0) a tile is 256 rows of one head,
+// with grouped-query attention the heads of a group ride on one staging of their common keys.
 // lds: at least tile_lds_bytes<D>() bytes of workgroup LDS, 16-byte aligned.
 template <int D>
-__device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& it, int head, uint16_t* lds) {
+__device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& it, int th, uint16_t* lds) {
   using G = TG<D>;
 
   const int H = p.num_heads;
+  const int Hk = p.num_kv_heads;
+  const int gs = p.tile_g_shift;
+  const int head0 = th << gs;
+  const int kvh = head0 / p.group;
+  const int n_rows_t = it.n_rows << gs;               // rows of the tile: query rows x heads of the group
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -242,15 +255,16 @@ __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& i
   const int hl = lane >> 5;
 
   // ---- this wave's Q^T operand (registers for the whole item) and causal limits
-  const int r = 32 * w + col;                       // row inside the item
-  const bool row_ok = r < it.n_rows;
-  const int r_eff = row_ok ? r : it.n_rows - 1;     // dead rows mirror the last live one
-  const int pos = it.pos0 + r_eff;                  // last visible key of this lane's row
-  const int wave_pos_lo = it.pos0 + min(32 * w, it.n_rows - 1);        // smallest limit in the wave
-  const int wave_pos_hi = it.pos0 + min(32 * w + 31, it.n_rows - 1);   // largest limit in the wave
+  const int r = 32 * w + col;                       // row inside the tile
+  const int r_eff = min(r, n_rows_t - 1);           // dead rows mirror the last live one
+  const int pos = it.pos0 + (r_eff >> gs);          // last visible key of this lane's row
+  const int wave_pos_lo = it.pos0 + min((32 * w) >> gs, it.n_rows - 1);        // smallest limit in the wave
+  const int wave_pos_hi = it.pos0 + min((32 * w + 31) >> gs, it.n_rows - 1);   // largest limit in the wave
   bf16x8 qreg[G::kQSteps];
   {
-    const uint16_t* qp = p.q + ((int64_t)(it.qrow0 + r_eff) * H + head) * D + 8 * hl;
+    const int qr = r_eff >> gs;                     // query row inside the item
+    const int head = head0 + (r_eff & ((1 << gs) - 1));
+    const uint16_t* qp = p.q + ((int64_t)(it.qrow0 + qr) * H + head) * D + 8 * hl;
 #pragma unroll
     for (int s = 0; s < G::kQSteps; ++s) qreg[s] = *(const bf16x8*)(qp + 16 * s);
   }
@@ -288,16 +302,16 @@ __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& i
   Staging<D> st[PFD];
   int ids[4];
   tile_ids(0, ids);
-  fetch_tile<D>(st[0], pool, ids, head, H, tid);
+  fetch_tile<D>(st[0], pool, ids, kvh, Hk, tid);
   if (PFD == 2 && n_tiles > 1) {
     tile_ids(1, ids);
-    fetch_tile<D>(st[PFD - 1], pool, ids, head, H, tid);
+    fetch_tile<D>(st[PFD - 1], pool, ids, kvh, Hk, tid);
   }
   stage_half<D>(st[0], 0, lds, lds + kTileK * G::kKStride, tid, it.k_end - it.k_begin);
   stage_half<D>(st[0], 1, lds, lds + kTileK * G::kKStride, tid, it.k_end - it.k_begin);
   if (PFD < n_tiles) {
     tile_ids(PFD, ids);
-    fetch_tile<D>(st[0], pool, ids, head, H, tid);
+    fetch_tile<D>(st[0], pool, ids, kvh, Hk, tid);
     if (PFD + 1 < n_tiles) tile_ids(PFD + 1, ids);
   }
   __syncthreads();
@@ -317,7 +331,7 @@ __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& i
       stage_half<D>(sreg, 1, nks, nvs, tid, n_valid_next);
     }
     if (t + 1 + PFD < n_tiles) {
-      fetch_tile<D>(sreg, pool, ids, head, H, tid);
+      fetch_tile<D>(sreg, pool, ids, kvh, Hk, tid);
       if (t + 2 + PFD < n_tiles) tile_ids(t + 2 + PFD, ids);
     }
     __syncthreads();
@@ -333,10 +347,13 @@ __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& i
 
   // ---- epilogue: lane holds O^T[d][col] for d = 32 dt + 8 (i/4) + 4 hl + i%4
   l += __shfl_xor(l, 32);
-  if (row_ok) {
+  // (row coordinates are worked out again here rather than kept in registers across the key loop)
+  if (r < n_rows_t) {
+    const int qr = r >> gs;
+    const int head = head0 + (r & ((1 << gs) - 1));
     if (it.slot0 < 0) {
       const float inv = 1.0f / l;
-      uint16_t* op = p.out + ((int64_t)(it.qrow0 + r) * H + head) * D;
+      uint16_t* op = p.out + ((int64_t)(it.qrow0 + qr) * H + head) * D;
 #pragma unroll
       for (int dt = 0; dt < G::kDTiles; ++dt)
 #pragma unroll
@@ -348,7 +365,7 @@ __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& i
           *(bf16x4*)(op + d) = o;
         }
     } else {
-      const int64_t ps = (int64_t)(it.slot0 + r * it.nparts) * H + head;
+      const int64_t ps = (int64_t)(it.slot0 + qr * it.nparts) * H + head;
       float* op = p.part_o + ps * D;
 #pragma unroll
       for (int dt = 0; dt < G::kDTiles; ++dt)

@@ -38,11 +38,16 @@ class AttnConfig:
     span_len: int = 0
     span_prefix: Tuple[int, int] = (0, 0)  # inclusive range of the cached prefix before the span
     span_ctx: Optional[Tuple[int, int]] = None  # if set: draw total context instead of prefix
+    num_kv_heads: int = 0                # 0: as many as query heads (multi-head attention)
+
+    @property
+    def kv_heads(self) -> int:
+        return self.num_kv_heads or self.num_heads
 
     @property
     def token_bytes(self) -> int:
-        """KV bytes per token for one layer (the paper's M, Section 3.2): K and V, all heads, bf16."""
-        return 2 * self.num_heads * self.head_dim * 2
+        """KV bytes per token for one layer (the paper's M, Section 3.2): K and V, all K/V heads, bf16."""
+        return 2 * self.kv_heads * self.head_dim * 2
 
     @property
     def block_bytes(self) -> int:
@@ -83,6 +88,10 @@ GPTJ_DECODE = AttnConfig("gptj_decode", 1, num_heads=16, head_dim=256, block_siz
 MIXED_13B = AttnConfig("mixed_13b", 2, num_heads=40, head_dim=128, block_size=16,
                        pool_blocks=65536, n_decode=128, decode_ctx=(256, 4096),
                        n_span=8, span_len=512, span_prefix=(1024, 4096))
+# Grouped-query shape of the paper's largest model (Section 5: Llama3-70B, 64 query heads over 8 K/V heads)
+GQA_70B = AttnConfig("gqa_70b", 5, num_heads=64, head_dim=128, block_size=16, pool_blocks=65536,
+                     n_decode=128, decode_ctx=(256, 4096), n_span=8, span_len=512, span_prefix=(1024, 4096),
+                     num_kv_heads=8)
 LONG_CTX = AttnConfig("long_ctx", 4, num_heads=32, head_dim=128, block_size=16,
                       pool_blocks=524288, n_decode=256, decode_ctx=(1024, 8192),
                       n_span=16, span_len=2048, span_prefix=(16384, 16384))
@@ -91,7 +100,7 @@ TINY_SWAP = SwapConfig("tiny_swap", 0, num_heads=4, head_dim=64, block_size=16,
 KV_SWAP = SwapConfig("kv_swap", 3, num_heads=40, head_dim=128, block_size=16,
                      pool_blocks=20000, n_move=2000)
 
-ATTN_CONFIGS: Dict[str, AttnConfig] = {c.name: c for c in (TINY, GPTJ_DECODE, MIXED_13B, LONG_CTX)}
+ATTN_CONFIGS: Dict[str, AttnConfig] = {c.name: c for c in (TINY, GPTJ_DECODE, MIXED_13B, LONG_CTX, GQA_70B)}
 SWAP_CONFIGS: Dict[str, SwapConfig] = {c.name: c for c in (TINY_SWAP, KV_SWAP)}
 
 
@@ -114,6 +123,11 @@ class Batch:
     block_tables: np.ndarray
     scale: float
     extra: dict = field(default_factory=dict)
+    num_kv_heads: int = 0                # 0: as many as query heads
+
+    @property
+    def kv_heads(self) -> int:
+        return self.num_kv_heads or self.num_heads
 
     @property
     def num_seqs(self) -> int:
@@ -129,7 +143,7 @@ class Batch:
 
     @property
     def token_bytes(self) -> int:
-        return 2 * self.num_heads * self.head_dim * 2
+        return 2 * self.kv_heads * self.head_dim * 2
 
     def kv_bytes(self) -> int:
         """Algorithmic KV bytes of the call: every sequence's context read once."""
@@ -181,12 +195,12 @@ def make_batch(cfg: AttnConfig, seed: Optional[int] = None) -> Batch:
         ctx.append(c)
         qlen.append(n)
     return assemble_batch(cfg.num_heads, cfg.head_dim, cfg.block_size, cfg.pool_blocks,
-                          ctx, qlen, r_ids)
+                          ctx, qlen, r_ids, num_kv_heads=cfg.num_kv_heads)
 
 
 def assemble_batch(num_heads: int, head_dim: int, block_size: int, pool_blocks: int,
                    ctx: List[int], qlen: List[int], rng: np.random.Generator,
-                   scale: Optional[float] = None) -> Batch:
+                   scale: Optional[float] = None, num_kv_heads: int = 0) -> Batch:
     """Build a Batch from explicit lengths; block ids come from one permutation of the pool."""
     ctx_a = np.asarray(ctx, dtype=np.int32)
     q_a = np.asarray(qlen, dtype=np.int32)
@@ -205,7 +219,8 @@ def assemble_batch(num_heads: int, head_dim: int, block_size: int, pool_blocks: 
     if len(ctx) > 1:
         q_start[1:] = np.cumsum(q_a)[:-1]
     sc = float(np.float32(1.0 / np.sqrt(np.float32(head_dim)))) if scale is None else float(scale)
-    return Batch(num_heads, head_dim, block_size, pool_blocks, ctx_a, q_a, q_start, tables, sc)
+    return Batch(num_heads, head_dim, block_size, pool_blocks, ctx_a, q_a, q_start, tables, sc,
+                 num_kv_heads=num_kv_heads)
 
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
@@ -239,7 +254,7 @@ def make_host_inputs(batch: Batch, seed: int, poison_unused: bool = True):
     each last block) holds the bf16 NaN pattern 0x7FFF, so any stray read shows up in the output.
     """
     r_pool, r_q = _streams(seed, 4)[2:4]
-    shp = pool_shape(batch.pool_blocks, batch.num_heads, batch.block_size, batch.head_dim)
+    shp = pool_shape(batch.pool_blocks, batch.kv_heads, batch.block_size, batch.head_dim)
     pool = randn_bf16(shp, r_pool)
     if poison_unused:
         poison_pool(pool, batch)
@@ -324,5 +339,5 @@ def compact_referenced(batch: Batch, seqs, fetch_blocks):
         off += nb
     sub = Batch(batch.num_heads, batch.head_dim, batch.block_size, len(ids),
                 batch.ctx_len[seqs].copy(), batch.q_len[seqs].copy(), batch.q_start[seqs].copy(),
-                tables, batch.scale)
+                tables, batch.scale, num_kv_heads=batch.num_kv_heads)
     return small, sub

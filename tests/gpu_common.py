@@ -41,10 +41,11 @@ class AttnRunner:
         return from_dev_bits(self.out)
 
 
-def make_pool(pool_bits: np.ndarray):
-    nb, two, H, Bs, D = pool_bits.shape
+def make_pool(pool_bits: np.ndarray, num_heads: int = 0):
+    """pool_bits [blocks][2][Hkv][B][D]; num_heads = query heads (0: as many as K/V heads)."""
+    nb, two, Hkv, Bs, D = pool_bits.shape
     t = to_dev_bits(pool_bits)
-    return B.KvPool.from_tensor(t, H, D, Bs), t
+    return B.KvPool.from_tensor(t, num_heads or Hkv, D, Bs, num_kv_heads=Hkv), t
 
 
 def max_abs_err(out_bits: np.ndarray, want_f64: np.ndarray) -> float:

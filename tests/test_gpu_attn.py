@@ -18,7 +18,7 @@ TOL = 1e-2   # bf16 output, fp32 accumulation (the stated bar for this path)
 def _check_batch(batch, seed, tunings=((0, 0, 0),), tol=TOL):
     pool_bits, q_bits = W.make_host_inputs(batch, seed, poison_unused=True)
     want = oracle.attn_batch(batch, pool_bits, q_bits)
-    pool, keep = make_pool(pool_bits)
+    pool, keep = make_pool(pool_bits, batch.num_heads)
     errs = []
     for tn in tunings:
         if isinstance(tn, dict):
@@ -80,6 +80,20 @@ def test_every_launch_path(D, H):
     tunings += [dict(row_variant=v, row_launch=rl) for v in (1, 2, 3) for rl in (1, 2)]
     tunings += [dict(span_kernel=1, row_launch=rl, decode_part_tokens=128, span_part_tokens=128) for rl in (1, 2, 3)]
     _check_batch(batch, 900 + D, tunings=tunings)
+
+
+@pytest.mark.parametrize("H,Hkv,D", [(8, 2, 64), (8, 1, 128), (16, 2, 128), (64, 8, 128), (6, 2, 128), (4, 2, 256), (64, 1, 64)])
+def test_grouped_query_attention(H, Hkv, D):
+    """H query heads over Hkv K/V heads: decode rows and spans, whole-row and split-KV plans, head groups
+    of 2 to 32 on the MFMA path (keys staged once per group), a group of 3 (not a power of two) and one
+    of 64 on the per-head path, and the row-by-row plan."""
+    ctx = [700, 33, 300, 1, 129, 1000, 64, 515, 2100, 90, 17, 40]
+    qlen = [200, 1, 300, 1, 128, 257, 1, 130, 1, 1, 1, 40]
+    rng = np.random.default_rng(H * 7 + Hkv + D)
+    batch = W.assemble_batch(H, D, 16, 512, ctx, qlen, rng, num_kv_heads=Hkv)
+    tunings = [dict(), dict(decode_part_tokens=64, span_part_tokens=128), dict(decode_part_tokens=256, span_part_tokens=64),
+               dict(span_kernel=1), dict(span_kernel=1, decode_part_tokens=128), dict(serial_spans=1)]
+    _check_batch(batch, 300 + H + Hkv + D, tunings=tunings)
 
 
 def test_caller_stream_and_back_to_back_calls():

@@ -48,7 +48,8 @@ def test_pool_init_validation():
     p.close()
     for kw, code in [(dict(cfg=B.make_cfg(64, 4, 96)), B.IC_EUNSUPPORTED),
                      (dict(cfg=B.make_cfg(64, 4, 64, block_size=32)), B.IC_EUNSUPPORTED),
-                     (dict(cfg=B.make_cfg(64, 8, 64, num_kv_heads=2)), B.IC_EUNSUPPORTED),
+                     (dict(cfg=B.make_cfg(64, 8, 64, num_kv_heads=3)), B.IC_EINVAL),      # heads must divide
+                     (dict(cfg=B.make_cfg(64, 4, 64, num_kv_heads=8)), B.IC_EINVAL),
                      (dict(cfg=B.make_cfg(64, 4, 64, dtype=1)), B.IC_EUNSUPPORTED),
                      (dict(cfg=B.make_cfg(0, 4, 64)), B.IC_EINVAL),
                      (dict(ptr=0x10008), B.IC_EALIGN),
@@ -296,3 +297,42 @@ def test_saturation_point_and_schedule_match_the_oracle():
     assert B.schedule_intercepted([1.0], [float("nan")], [5], 10)[0] == B.IC_EINVAL
     assert B.schedule_intercepted([1.0], [1.0], [-5], 10)[0] == B.IC_EINVAL
     assert B.schedule_intercepted([1.0], [1.0], [5], -1)[0] == B.IC_EINVAL
+
+
+def test_kernel_register_budgets():
+    """The side-by-side launch of the mixed batch needs, per SIMD, two waves of the persistent tile kernel
+    and one of the slim row kernel resident together: 2 x 216 + 80 = 512 registers per lane.  Read the
+    compiler's resource report for both kernels (head_dim 64 and 128) and for spills in the MFMA kernels."""
+    import shutil
+    import subprocess
+    import tempfile
+    if not shutil.which("hipcc"):
+        pytest.skip("hipcc not on PATH")
+    csrc = os.path.join(ROOT, "paper_2402_01869_amd", "csrc")
+    usage = {}
+    with tempfile.TemporaryDirectory() as tmp:
+        for src in ("attn_tile.hip", "attn_row.hip"):
+            r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature",
+                                "-Xclang", "-packed-fp32-ops", "-Rpass-analysis=kernel-resource-usage", "-c",
+                                os.path.join(csrc, src), "-o", os.path.join(tmp, src + ".o")],
+                               capture_output=True, text=True)
+            assert r.returncode == 0, r.stderr[-2000:]
+            name = None
+            for line in r.stderr.splitlines():
+                m = re.search(r"Function Name: (\S+)", line)
+                if m:
+                    name = m.group(1); usage[name] = {}
+                m = re.search(r"\s(VGPRs|VGPRs Spill|ScratchSize \[bytes/lane\]): (\d+)", line)
+                if m and name:
+                    usage[name][m.group(1)] = int(m.group(2))
+    def find(kernel, dim):
+        hits = [u for n, u in usage.items() if kernel in n and f"ILi{dim}E" in n]
+        assert len(hits) == 1, (kernel, dim, list(usage))
+        return hits[0]
+    for dim in (64, 128):
+        assert find("tile_persist_kernel", dim)["VGPRs"] <= 216
+        assert find("row_persist_slim_kernel", dim)["VGPRs"] <= 80
+    for dim in (64, 128, 256):
+        assert find("tile_attn_kernel", dim)["VGPRs Spill"] == 0
+    for dim in (64, 128):
+        assert find("tile_persist_kernel", dim)["VGPRs Spill"] == 0
