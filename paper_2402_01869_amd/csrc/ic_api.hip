@@ -131,7 +131,8 @@ struct PlanSizes {
   int row_part, span_part, tile_rows;  // tile_rows: QUERY rows per tile item
   int tile_g_shift;                    // log2 of the query heads one tile workgroup serves
   bool spans_as_rows;
-  bool decode_as_tiles;                // grouped-query pools: the heads of a group share the keys on the MFMA path
+  bool decode_as_tiles;                // grouped pools, span_kernel = 2: decode rows as one-row tile items
+  bool decode_as_group;                // grouped pools: decode rows stay row items, run by the group kernel
   size_t off_ctr, off_bt_off, off_bt_flat, off_row, off_tile, off_merge, image_bytes;
   size_t off_part_o, off_part_ml, total_bytes;
 };
@@ -142,7 +143,8 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   std::memset(&ps, 0, sizeof ps);
   // Grouped-query attention: the G = H / Hkv query heads of a group read the same keys.  When G is a
   // power of two up to 32, a tile workgroup takes all of them (G rows per query row), so keys are
-  // staged once per group, and decode rows (G rows of one query token) go to the MFMA path too.
+  // staged once per group, and decode rows (G rows of one query token) go to the matrix cores too:
+  // as row items run by the group kernel, or (span_kernel = 2) as one-row tile items.
   const int G = pool->cfg.num_heads / pool->cfg.num_kv_heads;
   ps.tile_g_shift = 0;
   if (G >= 2 && G <= 32 && (G & (G - 1)) == 0)
@@ -155,7 +157,8 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   ps.row_part = std::min(ps.row_part, kMaxRowPart);
   ps.span_part = t.span_part_tokens > 0 ? round64(t.span_part_tokens) : kDefaultSpanPart;
   ps.spans_as_rows = (t.span_kernel == 1);  // default: MFMA tiles
-  ps.decode_as_tiles = ps.tile_g_shift > 0 && t.span_kernel != 1;
+  ps.decode_as_tiles = ps.tile_g_shift > 0 && t.span_kernel == 2;
+  ps.decode_as_group = ps.tile_g_shift > 0 && t.span_kernel == 0;
   ic_plan_info& in = ps.info;
   for (int s = 0; s < d->num_seqs; ++s) {
     const int c = d->ctx_len[s], n = d->q_len[s];
@@ -478,7 +481,10 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
   // workgroup of each per CU, the tile kernel on the pool's second stream (forked from and joined
   // back into the caller's stream by events).  serial_spans = 1, and head_dim 256 (whose tile
   // workgroup leaves no registers for a neighbour), run one kernel after the other instead.
-  const bool beside = p.n_tile_items > 0 && p.n_row_items > 0 && !pool->tune.serial_spans && D <= 128;
+  // Grouped pools run the tile kernel, then the group kernel (measured: as two ordinary launches on
+  // two streams they overlap by 2 %, not worth a second queue).
+  const bool beside = p.n_tile_items > 0 && p.n_row_items > 0 && !pool->tune.serial_spans && D <= 128 &&
+                      !ps.decode_as_group;
   if (beside) {
     if (!pool->side) {
       if (hipStreamCreateWithFlags(&pool->side, hipStreamNonBlocking) != hipSuccess) return IC_EHIP;
@@ -502,7 +508,10 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
       ProfScope ps_(pool, IC_K_TILE, st);
       if (launch_tile_kernel(p, D, st) != hipSuccess) return IC_EHIP;
     }
-    if (p.n_row_items > 0) {
+    if (p.n_row_items > 0 && ps.decode_as_group) {
+      ProfScope ps_(pool, IC_K_ROW, st);
+      if (launch_group_kernel(p, D, st) != hipSuccess) return IC_EHIP;
+    } else if (p.n_row_items > 0) {
       ProfScope ps_(pool, IC_K_ROW, st);
       const int slots = pool->tune.row_slots > 0 ? pool->tune.row_slots : pool->num_cus;
       const hipError_t e = pool->tune.row_launch == 3 && D <= 128 ? launch_row_persist_slim(p, D, slots, st)

@@ -89,6 +89,7 @@ hipError_t launch_row_persist_slim(const AttnParams& p, int head_dim, int slots,
 hipError_t launch_tile_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st);
 hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_merge_kernel(const AttnParams& p, int head_dim, hipStream_t st);
+hipError_t launch_group_kernel(const AttnParams& p, int head_dim, hipStream_t st);  // row items x K/V heads
 // Rows of k_new / v_new ([rows][H][D] bf16) into the pool at slot dst[row] (block * 16 + slot; < 0: skip).
 hipError_t launch_append(void* pool, const void* k_new, const void* v_new, const int32_t* dev_dst, int32_t rows,
                          int num_heads, int head_dim, hipStream_t st);
