@@ -14,6 +14,7 @@ namespace {
 constexpr int kStagingSlots = 4;       // pinned host buffers cycled by successive calls
 constexpr int kDefaultRowPart = 2048;  // keys per decode work item (512 for head_dim 256): ~0.5-1 MiB of KV per head
 constexpr int kDefaultSpanPart = 8192; // keys per span-tile work item (partials of 256 rows are costly)
+constexpr int kUnsplitWorkgroups = 1024;  // tile workgroups (4 per CU) from which spans are not split at all
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -156,6 +157,16 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
                                          : (pool->cfg.head_dim >= 256 ? kDefaultRowPart / 4 : kDefaultRowPart);
   ps.row_part = std::min(ps.row_part, kMaxRowPart);
   ps.span_part = t.span_part_tokens > 0 ? round64(t.span_part_tokens) : kDefaultSpanPart;
+  if (t.span_part_tokens == 0) {
+    // Splitting a span's keys buys parallelism at the price of fp32 partial results for every row
+    // and a merge pass (measured on the long-context shape: 7 % of the call).  When the unsplit query
+    // tiles already give every CU several workgroups, do not split.
+    int64_t tiles = 0;
+    for (int s = 0; s < d->num_seqs; ++s)
+      if (d->q_len[s] > 1) tiles += (d->q_len[s] + kTileRows - 1) / kTileRows;
+    const int64_t head_groups = pool->cfg.num_heads >> ps.tile_g_shift;
+    if (tiles * head_groups >= kUnsplitWorkgroups) ps.span_part = 1 << 30;
+  }
   ps.spans_as_rows = (t.span_kernel == 1);  // default: MFMA tiles
   ps.decode_as_tiles = ps.tile_g_shift > 0 && t.span_kernel == 2;
   ps.decode_as_group = ps.tile_g_shift > 0 && t.span_kernel == 0;

@@ -186,8 +186,9 @@ def test_mixed_13b_config_sampled():
 
 @pytest.mark.timeout(900)
 def test_long_context_config_sampled():
-    """Long-context stress at full size (128 GiB pool, 16 spans of 2048 rows on 16384-token prefixes,
-    split-KV path): every 4th decode sequence and a deterministic sample of span rows."""
+    """Long-context stress at full size (128 GiB pool, 16 spans of 2048 rows on 16384-token prefixes): every
+    4th decode sequence and a deterministic sample of span rows, under the default plan (decode rows split
+    over keys, spans not: there are workgroups enough) and with the spans' keys split too."""
     cfg = W.LONG_CTX
     free, total = torch.cuda.mem_get_info()
     need = cfg.pool_blocks * cfg.block_bytes + (8 << 30)
@@ -200,9 +201,14 @@ def test_long_context_config_sampled():
     pool = B.KvPool.from_tensor(pool_t, cfg.num_heads, cfg.head_dim)
     r = AttnRunner(pool, batch, q_bits, flags=B.IC_FLAG_TRUSTED)
     info = pool.plan_query(r.desc)
-    assert info["partial_slots"] > 0 and info["tile_items"] > 16 * 16   # split-KV really in use
-    out = r.run()
-    assert np.isfinite(W.bf16_bits_to_f64(out)).all()
+    assert info["partial_slots"] > 0 and info["tile_items"] == 16 * 8   # decode rows split, spans whole
+    outs = {"default": r.run().copy()}
+    pool.set_tuning(span_part_tokens=8192)
+    info = pool.plan_query(r.desc)
+    assert info["tile_items"] == 16 * 8 * 3                             # every query tile in three key partitions
+    outs["split spans"] = r.run().copy()
+    for o in outs.values():
+        assert np.isfinite(W.bf16_bits_to_f64(o)).all()
 
     def fetch(ids):
         return from_dev_bits(pool_t.view(torch.int16)[torch.from_numpy(ids).to(DEV)])
@@ -220,8 +226,8 @@ def test_long_context_config_sampled():
         want = oracle.paged_attn_items(small, sub.ctx_len, sub.q_len, sub.q_start, sub.block_tables, q_bits,
                                        sub.scale, iseq, irow)
         grow = [int(sub.q_start[j]) + i for j, i in zip(iseq, irow)]
-        got = W.bf16_bits_to_f64(out[grow])
-        worst = max(worst, float(np.abs(got - want).max()))
+        for o in outs.values():
+            worst = max(worst, float(np.abs(W.bf16_bits_to_f64(o[grow]) - want).max()))
         del small
     assert worst <= TOL, worst
     pool.close()
