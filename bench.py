@@ -21,10 +21,12 @@ import numpy as np
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
 # command, scaled by the pack kernel's known 640 000 KiB (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 on this GPU);
-# figures and commands in profiles/row_and_tile_persist_kernels_mixed_13b.md and
-# profiles/row_persist_kernel_gptj_decode.md.  Only valid for the default launch plan of these workloads.
-MEASURED_TRAFFIC_BYTES = {"mixed_13b/row": (2836516 * 2.0 + 4254) * 1024,
-                          "gptj_decode/row": (660525 * 2.0 + 3277) * 1024}
+# figures and commands in profiles/row_and_tile_persist_kernels_mixed_13b.md,
+# profiles/row_persist_kernel_gptj_decode.md and profiles/group_and_tile_kernels_gqa_70b.md.  Only valid for the
+# default launch plan of these workloads.
+MEASURED_TRAFFIC_BYTES = {"mixed_13b/row": (2836506 * 2.0 + 4254) * 1024,
+                          "gptj_decode/row": (660656 * 2.0 + 3278) * 1024,
+                          "gqa_70b/row": (537675 * 2.0 + 5144) * 1024}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
 
@@ -515,8 +517,10 @@ def main():
     if prof["row"]["launches"]:
         dom_bytes = kv_bytes if plan["tile_items"] == 0 else dec_bytes
         ach = dom_bytes / (avg_ms("row") * 1e-3) / 1e9
-        beside = prof["tile"]["launches"] > 0 and not args.serial_spans and D <= 128
-        name = ("row_persist_slim_kernel" if beside else
+        G = H // acfg.kv_heads
+        grouped = 2 <= G <= 32 and G & (G - 1) == 0 and args.span_kernel == 0   # decode rows on the group kernel
+        beside = prof["tile"]["launches"] > 0 and not args.serial_spans and D <= 128 and not grouped
+        name = ("group_attn_kernel" if grouped else "row_persist_slim_kernel" if beside else
                 "row_attn_kernel" if args.row_launch == 1 else "row_persist_kernel")
         roofline = {"kernel": name, "runs_beside": "tile_persist_kernel" if beside else None,
                     "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
