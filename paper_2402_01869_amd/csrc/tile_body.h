@@ -316,6 +316,7 @@ __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& i
   }
   __syncthreads();
 
+  const bool feed_first = TW<D>::kWaves == 8 && (w & 4) != 0;  // wave-uniform
   // step t with its register set fixed at compile time (RS = (t + 1) % PFD holds tile t + 1)
   auto step = [&](int t, Staging<D>& sreg) {
     const int kt = it.k_begin + t * kTileK;
@@ -323,17 +324,25 @@ __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& i
     const uint16_t* vs = ks + kTileK * G::kKStride;
     uint16_t* nks = lds + ((t + 1) & 1) * kBuf;
     uint16_t* nvs = nks + kTileK * G::kKStride;
+    // Waves w and w + 4 share a SIMD.  The first does its arithmetic, then its copy and loads; the
+    // second the other way round, so that between two barriers one wave of a SIMD is in the matrix
+    // and vector pipes while the other waits on memory and LDS writes, instead of both doing the
+    // same thing at the same time.
+    auto feed = [&]() {
+      if (t + 1 < n_tiles) {
+        const int n_valid_next = it.k_end - (kt + kTileK);
+        stage_half<D>(sreg, 0, nks, nvs, tid, n_valid_next);
+        stage_half<D>(sreg, 1, nks, nvs, tid, n_valid_next);
+      }
+      if (t + 1 + PFD < n_tiles) {
+        fetch_tile<D>(sreg, pool, ids, kvh, Hk, tid);
+        if (t + 2 + PFD < n_tiles) tile_ids(t + 2 + PFD, ids);
+      }
+    };
+    if (feed_first) feed();
     if (kt <= wave_pos_hi)  // otherwise every key of the tile is in this wave's future
       wave_step<D>(ks, vs, qreg, acc_o, m, l, kt, pos, col, hl, sc, kt + kTileK - 1 > wave_pos_lo);
-    if (t + 1 < n_tiles) {
-      const int n_valid_next = it.k_end - (kt + kTileK);
-      stage_half<D>(sreg, 0, nks, nvs, tid, n_valid_next);
-      stage_half<D>(sreg, 1, nks, nvs, tid, n_valid_next);
-    }
-    if (t + 1 + PFD < n_tiles) {
-      fetch_tile<D>(sreg, pool, ids, kvh, Hk, tid);
-      if (t + 2 + PFD < n_tiles) tile_ids(t + 2 + PFD, ids);
-    }
+    if (!feed_first) feed();
     __syncthreads();
   };
   if constexpr (PFD == 2) {
