@@ -109,14 +109,19 @@ __device__ __forceinline__ void group_step(const uint16_t* ks, const uint16_t* v
   const bool grew = m_new > m;
   const float alpha = __builtin_amdgcn_exp2f(m - m_new);
   m = m_new;
+  // weights rounded to bf16 in pairs and summed as rounded (bf16 dot product with (1, 1)): the
+  // normaliser counts exactly what the matrix core multiplies
   float psum = 0.f;
   bf16x8 pb[2];
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[i], sc, -m_new));
-    const __bf16 pr = (__bf16)pv;  // the normaliser sums the weights as the matrix core sees them
-    psum += (float)pr;
-    pb[i / 8][i % 8] = pr;
+  for (int i = 0; i < 16; i += 2) {
+    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[i], sc, -m_new));
+    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[i + 1], sc, -m_new));
+    const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
+    psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+    pb[i / 8][i % 8] = pr[0];
+    pb[i / 8][i % 8 + 1] = pr[1];
   }
   l = l * alpha + psum;
   if (__builtin_amdgcn_ballot_w64(grew) != 0) {

@@ -30,6 +30,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 constexpr float kNegBig = -1.0e30f;
 constexpr int kTileK = 64;    // keys per staged tile
@@ -179,19 +180,23 @@ __device__ __forceinline__ void wave_step(const uint16_t* ks, const uint16_t* vs
   const bool grew = m_new > m;
   const float alpha = __builtin_amdgcn_exp2f(m - m_new);
   m = m_new;
+  // Weights: rounded to bf16 in pairs (one v_cvt_pk_bf16_f32), and summed AS ROUNDED by a bf16 dot
+  // product with (1, 1): the normaliser then counts exactly what the matrix core will multiply, so
+  // the output stays an exact convex combination of the values and a row dominated by one key
+  // (short contexts) does not inherit the 2^-9 relative rounding error of its weight.
   float psum = 0.f;
   bf16x8 pb[4];
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
   for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[tt][i], sc, -m_new));
-      // The normaliser sums the weights as the matrix core will see them (rounded to bf16): the
-      // output stays an exact convex combination of the values, and a row dominated by one key
-      // (short contexts) does not inherit the 2^-9 relative rounding error of its weight.
-      const __bf16 pr = (__bf16)pv;
-      psum += (float)pr;
-      pb[2 * tt + i / 8][i % 8] = pr;
+    for (int i = 0; i < 16; i += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[tt][i], sc, -m_new));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[tt][i + 1], sc, -m_new));
+      const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
+      psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+      pb[2 * tt + i / 8][i % 8] = pr[0];
+      pb[2 * tt + i / 8][i % 8 + 1] = pr[1];
     }
   l = l * alpha + psum;
   if (__builtin_amdgcn_ballot_w64(grew) != 0) {  // rescale only when some row's maximum moved
