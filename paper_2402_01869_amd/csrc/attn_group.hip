@@ -105,9 +105,13 @@ __device__ __forceinline__ void group_step(const uint16_t* ks, const uint16_t* v
 #pragma unroll
   for (int i = 0; i < 16; ++i) tmax = __builtin_fmaxf(tmax, s_acc[i]);
   tmax = __builtin_fmaxf(tmax, __shfl_xor(tmax, 32));
-  const float m_new = __builtin_fmaxf(m, tmax * sc);
-  const bool grew = m_new > m;
-  const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+  // Lazy reference: the running maximum m only has to bound the scores loosely.  It is moved (and the
+  // accumulators rescaled, 16 multiplies per 32 output rows) only when a score exceeds it by more than
+  // kLazyLog2; until then weights may reach 2^kLazyLog2, which fp32 sums and bf16 weights hold easily.
+  const float m_cand = __builtin_fmaxf(m, tmax * sc);
+  const bool grew = m_cand > m + kLazyLog2;
+  const float m_new = grew ? m_cand : m;
+  const float alpha = grew ? __builtin_amdgcn_exp2f(m - m_cand) : 1.0f;
   m = m_new;
   // weights rounded to bf16 in pairs and summed as rounded (bf16 dot product with (1, 1)): the
   // normaliser counts exactly what the matrix core multiplies

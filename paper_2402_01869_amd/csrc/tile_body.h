@@ -33,6 +33,7 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 constexpr float kNegBig = -1.0e30f;
+constexpr float kLazyLog2 = 8.0f;  // slack of the online softmax's reference maximum, in log2 units
 constexpr int kTileK = 64;    // keys per staged tile
 // Waves (of 32 query rows each) per workgroup: tile_rows(D) / 32.  More rows per workgroup means
 // fewer workgroups re-reading the same keys from L2 / HBM.
@@ -176,9 +177,13 @@ __device__ __forceinline__ void wave_step(const uint16_t* ks, const uint16_t* vs
 #pragma unroll
     for (int i = 0; i < 16; ++i) tmax = __builtin_fmaxf(tmax, s_acc[tt][i]);
   tmax = __builtin_fmaxf(tmax, __shfl_xor(tmax, 32));
-  const float m_new = __builtin_fmaxf(m, tmax * sc);
-  const bool grew = m_new > m;
-  const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+  // Lazy reference: the running maximum m only has to bound the scores loosely.  It is moved (and the
+  // accumulators rescaled, 16 multiplies per 32 output rows) only when a score exceeds it by more than
+  // kLazyLog2; until then weights may reach 2^kLazyLog2, which fp32 sums and bf16 weights hold easily.
+  const float m_cand = __builtin_fmaxf(m, tmax * sc);
+  const bool grew = m_cand > m + kLazyLog2;
+  const float m_new = grew ? m_cand : m;
+  const float alpha = grew ? __builtin_amdgcn_exp2f(m - m_cand) : 1.0f;
   m = m_new;
   // Weights: rounded to bf16 in pairs (one v_cvt_pk_bf16_f32), and summed AS ROUNDED by a bf16 dot
   // product with (1, 1): the normaliser then counts exactly what the matrix core will multiply, so
