@@ -144,13 +144,17 @@ int ic_check_batch(const ic_pool_cfg* cfg, const ic_batch_desc* desc);
  * 0 keeps the built-in choice.  Smaller values force the split-KV path on short contexts. */
 typedef struct {
   int32_t decode_part_tokens; /* keys per work item of a decode row                          */
-  int32_t span_part_tokens;   /* keys per work item of a span's query tile                   */
-  int32_t span_kernel;        /* 0 = built-in choice, 1 = row-by-row vector kernel, 2 = MFMA tiles */
+  int32_t span_part_tokens;   /* keys per work item of a span's query tile (built-in: 8192, or no split at all
+                                 when the unsplit tiles already give every CU four workgroups) */
+  int32_t span_kernel;        /* 0 = built-in choice (spans: MFMA tiles; decode rows: vector kernel, or the MFMA
+                                 group kernel in a grouped-query pool), 1 = everything row by row on the vector
+                                 kernel, 2 = MFMA tiles, in a grouped-query pool also for decode rows */
   int32_t row_variant;        /* vector-kernel build: bit 0 = prefetch two tiles ahead, bit 1 = cached (not non-temporal) KV loads */
   int32_t serial_spans;       /* 1 = run the span kernel, then the row kernel, on the caller's stream instead of
                                  two persistent kernels side by side (the tile kernel on the pool's own stream) */
   int32_t row_launch;         /* single-role row kernel: 0 = built-in choice (persistent, one workgroup per CU),
-                                 1 = one workgroup per work item, 2 = persistent               */
+                                 1 = one workgroup per work item, 2 = persistent, 3 = persistent, the slim
+                                 build that runs beside the tile kernel (head_dim <= 128)     */
   int32_t row_slots;          /* resident workgroups of the persistent row kernel; 0 = one per CU */
   int32_t reserved[1];        /* must be 0                                                   */
 } ic_tuning;
