@@ -97,6 +97,31 @@ def test_grouped_query_attention(H, Hkv, D):
     _check_batch(batch, 300 + H + Hkv + D, tunings=tunings)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_batches_and_plans(seed):
+    """Seeded random shapes, length mixes and launch plans: multi-head and grouped pools, contexts from one
+    token to a few thousand, decode rows, short and long chunks, whole prefills, forced splits."""
+    rng = np.random.default_rng(9000 + seed)
+    D = int(rng.choice([64, 128, 128, 256]))
+    Hkv = int(rng.choice([1, 2, 3, 5, 8]))
+    G = int(rng.choice([1, 1, 2, 4, 8, 3])) if D < 256 else int(rng.choice([1, 2]))
+    H = Hkv * G
+    n_seq = int(rng.integers(3, 10))
+    ctx, qlen = [], []
+    for _ in range(n_seq):
+        c = int(rng.choice([1, 2, 15, 16, 17, int(rng.integers(1, 200)), int(rng.integers(200, 2500))]))
+        kind = rng.integers(0, 4)
+        q = 1 if kind == 0 else c if kind == 1 else int(rng.integers(1, min(c, 400) + 1))
+        ctx.append(c); qlen.append(q)
+    blocks = sum(-(-c // 16) for c in ctx) + 7
+    batch = W.assemble_batch(H, D, 16, blocks, ctx, qlen, rng, num_kv_heads=Hkv)
+    part = lambda: int(rng.choice([0, 64, 128, 256, 1024]))
+    tunings = [dict()] + [dict(decode_part_tokens=part(), span_part_tokens=part(), span_kernel=int(rng.integers(0, 3)),
+                               serial_spans=int(rng.integers(0, 2)), row_launch=int(rng.integers(0, 4)))
+                          for _ in range(3)]
+    _check_batch(batch, 9100 + seed, tunings=tunings)
+
+
 def test_caller_stream_and_back_to_back_calls():
     """Calls issued back to back on a caller's (non-default) stream, alternating two batches that share
     the pool's descriptor ring and side stream, give what each gives alone."""
