@@ -2,7 +2,9 @@
 // sequence's paged keys.  Here QK^T and PV are dense contractions (hundreds of rows share every
 // key), so they run on the matrix cores: v_mfma_f32_32x32x16_bf16, fp32 accumulation.
 //
-// One workgroup = one TileItem x one head: up to tile_rows(D) query rows, one wave per 32 rows.
+// One workgroup = one TileItem x one head group (one head with multi-head attention; with grouped
+// queries the G heads that share a K/V head): up to tile_rows(D) rows = query rows x heads of the
+// group, one wave per 32 rows.
 //   - K and V tiles of 64 keys (4 cache blocks, looked up in the block table) are fetched with
 //     16-byte coalesced loads into registers two tiles ahead, then staged in one of two LDS
 //     buffers and shared by all waves; one barrier per tile.
@@ -14,7 +16,7 @@
 //     operand (8 keys per lane per MFMA, slot j of lane half hl <-> key 8*(j/4) + 4*hl + j%4).
 //     V stays [key][dim] in LDS; the A operand (one dim, 8 keys per lane, in that key order) comes
 //     from two ds_read_b64_tr_b16 transpose loads, so no register transposition is needed.
-//   - Causality: row r of the item sits at position pos0 + r and sees keys <= that position.
+//   - Causality: query row r of the item sits at position pos0 + r and sees keys <= that position.
 //     Only tiles that straddle a wave's diagonal are masked; tiles beyond it are skipped.
 // Dead slots (keys >= k_end, possibly NaN) get score -inf by select and V = 0 in LDS.
 #pragma once
