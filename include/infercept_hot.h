@@ -136,6 +136,22 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
 int kv_write_span(ic_pool* pool, const ic_batch_desc* desc, const void* dev_k_new, const void* dev_v_new,
                   void* hip_stream);
 
+/*
+ * Plan once, run for every layer.  One iteration's batch (Section 4.3) is the same for all layers of
+ * the model; only the cache (one pool per layer), q and out change.  paged_attn_plan_create validates
+ * and plans the batch for `pool`'s shape and tuning and uploads the descriptor image into
+ * dev_workspace on hip_stream; paged_attn_planned then runs the attention of any pool of that shape
+ * and tuning (IC_EINVAL otherwise) with nothing but kernel launches.  The workspace belongs to the
+ * plan until paged_attn_plan_destroy; its partial-result area is reused by every run, so runs of one
+ * plan must be ordered on one stream (after the stream the plan was created on has passed the
+ * upload).  Results are those of paged_attn_mixed, bit for bit.
+ */
+typedef struct ic_plan ic_plan;
+int paged_attn_plan_create(ic_pool* pool, const ic_batch_desc* desc, void* dev_workspace, size_t workspace_bytes,
+                           void* hip_stream, ic_plan** out);
+int paged_attn_planned(ic_pool* pool, const ic_plan* plan, const void* dev_q, void* dev_out, void* hip_stream);
+int paged_attn_plan_destroy(ic_plan* plan);
+
 /* Host-only validation of a descriptor against a pool shape (what paged_attn_mixed checks when
  * IC_FLAG_TRUSTED is clear).  Touches no GPU state. */
 int ic_check_batch(const ic_pool_cfg* cfg, const ic_batch_desc* desc);

@@ -32,6 +32,7 @@ EXPORTS = (
     "ic_host_alloc", "ic_host_free", "ic_swap_limit_tokens", "ic_swap_schedule", "kv_write_span",
     "ic_tfwd_eval", "ic_waste_discard", "ic_waste_preserve", "ic_waste_swap", "ic_waste_chunked_discard",
     "ic_chunk_tokens", "ic_chunk_count", "ic_saturation_point", "ic_schedule_intercepted",
+    "paged_attn_plan_create", "paged_attn_planned", "paged_attn_plan_destroy",
 )
 IC_ACT_NONE, IC_ACT_PRESERVE, IC_ACT_DISCARD = 0, 1, 2
 IC_SWAP_OUT, IC_SWAP_IN = 0, 1
@@ -112,6 +113,9 @@ def lib():
         L.paged_attn_mixed_workspace_bytes.restype = C.c_size_t
         L.paged_attn_mixed.argtypes = [vp, C.POINTER(BatchDesc), vp, vp, vp, C.c_size_t, vp]
         L.kv_write_span.argtypes = [vp, C.POINTER(BatchDesc), vp, vp, vp]
+        L.paged_attn_plan_create.argtypes = [vp, C.POINTER(BatchDesc), vp, C.c_size_t, vp, C.POINTER(vp)]
+        L.paged_attn_planned.argtypes = [vp, vp, vp, vp, vp]
+        L.paged_attn_plan_destroy.argtypes = [vp]
         L.ic_check_batch.argtypes = [C.POINTER(PoolCfg), C.POINTER(BatchDesc)]
         L.ic_pool_set_tuning.argtypes = [vp, C.POINTER(Tuning)]
         L.ic_plan_query.argtypes = [vp, C.POINTER(BatchDesc), C.POINTER(PlanInfo)]
@@ -264,6 +268,20 @@ class KvPool:
             raise InferceptError(rc, "paged_attn_mixed")
         return int(rc)
 
+    def plan_create(self, desc: HostDesc, ws_ptr: int, ws_bytes: int, stream: int = 0) -> "AttnPlan":
+        h = C.c_void_p()
+        rc = lib().paged_attn_plan_create(self._h, C.byref(desc.struct), C.c_void_p(ws_ptr), int(ws_bytes),
+                                          C.c_void_p(stream), C.byref(h))
+        if rc != IC_OK:
+            raise InferceptError(rc, "paged_attn_plan_create")
+        return AttnPlan(h)
+
+    def paged_attn_planned(self, plan: "AttnPlan", q_ptr: int, out_ptr: int, stream: int = 0, check: bool = True) -> int:
+        rc = lib().paged_attn_planned(self._h, plan._h, C.c_void_p(q_ptr), C.c_void_p(out_ptr), C.c_void_p(stream))
+        if check and rc != IC_OK:
+            raise InferceptError(rc, "paged_attn_planned")
+        return int(rc)
+
     def kv_write_span(self, desc: HostDesc, k_ptr: int, v_ptr: int, stream: int = 0, check: bool = True) -> int:
         rc = lib().kv_write_span(self._h, C.byref(desc.struct), C.c_void_p(k_ptr), C.c_void_p(v_ptr), C.c_void_p(stream))
         if check and rc != IC_OK:
@@ -314,6 +332,24 @@ def swap_schedule(total_blocks: int, block_size: int, limits):
     used = int(lib().ic_swap_schedule(int(total_blocks), int(block_size), lim.ctypes.data_as(i64p),
                                       lim.shape[0], out.ctypes.data_as(i64p)))
     return used, out
+
+
+class AttnPlan:
+    """Handle of a planned batch (descriptor image resident in the caller's workspace)."""
+
+    def __init__(self, handle):
+        self._h = handle
+
+    def close(self):
+        if self._h:
+            lib().paged_attn_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class PinnedBuffer:

@@ -39,6 +39,7 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_persist_kernel(AttnParams 
     row_body<D, PF, true>(p, it, (int)(idx - item * (uint32_t)H), lds);
     __syncthreads();  // the body leaves LDS in use until every wave is through
   }
+  queue_leave(p.counters, kCtrRowQueue, 1, -1, kCtrRowLeft);
 }
 
 // Split-KV merge: out = sum_p o_p 2^(m_p - m) / sum_p l_p 2^(m_p - m), m = max_p m_p.
@@ -110,6 +111,7 @@ __global__ __launch_bounds__(kRowWaves * 64, 6) void row_persist_slim_kernel(Att
     row_body<D, 0, true>(p, it, (int)(idx - item * (uint32_t)H), lds);
     __syncthreads();
   }
+  queue_leave(p.counters, kCtrRowQueue, 1, -1, kCtrRowLeft);
 }
 
 hipError_t launch_row_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st) {

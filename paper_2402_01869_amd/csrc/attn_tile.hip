@@ -32,12 +32,12 @@ __global__ __launch_bounds__(TW<D>::kThreads, (D <= 128 ? 2 : 1)) void tile_pers
   __shared__ __attribute__((aligned(16))) uint16_t lds[tile_lds_bytes<D>() / 2];
   __shared__ int s_next;
   const int H = p.num_heads >> p.tile_g_shift;               // head groups
-  const bool per_xcd = H >= 8;   // with fewer head groups than XCDs, one shared queue (counters[9]) instead
+  const bool per_xcd = H >= 8;   // with fewer head groups than XCDs, one shared queue instead
   const uint32_t x = blockIdx.x & 7u;
   const uint32_t heads_x = (uint32_t)(H - (int)x + 7) / 8u;  // head groups congruent to x mod 8
   const uint32_t n_t = (uint32_t)p.n_tile_items * (per_xcd ? heads_x : (uint32_t)H);
   for (;;) {
-    if (threadIdx.x == 0) s_next = atomicAdd(&p.counters[per_xcd ? x : 9u], 1);
+    if (threadIdx.x == 0) s_next = atomicAdd(&p.counters[per_xcd ? x : (uint32_t)kCtrTileShared], 1);
     __syncthreads();
     const uint32_t idx = (uint32_t)s_next;
     __syncthreads();  // s_next is rewritten at the top of the next round
@@ -55,6 +55,7 @@ __global__ __launch_bounds__(TW<D>::kThreads, (D <= 128 ? 2 : 1)) void tile_pers
     tile_body<D>(p, it, (int)th, lds);
     __syncthreads();  // the body leaves LDS in use until every wave is through
   }
+  queue_leave(p.counters, 0, 8, kCtrTileShared, kCtrTileLeft);
 }
 
 }  // namespace

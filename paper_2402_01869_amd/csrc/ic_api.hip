@@ -140,6 +140,18 @@ struct PlanSizes {
 
 int round64(int x) { return (x + 63) / 64 * 64; }
 
+}  // namespace
+
+struct ic_plan {
+  PlanSizes ps;
+  ic_pool_cfg cfg;   // shape the plan was made for
+  ic_tuning tune;    // launch knobs it was made with
+  float scale;
+  char* ws;          // the caller's workspace: descriptor image + partial results
+};
+
+namespace {
+
 void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   std::memset(&ps, 0, sizeof ps);
   // Grouped-query attention: the G = H / Hkv query heads of a group read the same keys.  When G is a
@@ -434,29 +446,24 @@ size_t paged_attn_mixed_workspace_bytes(const ic_pool* pool, const ic_batch_desc
   return ps.total_bytes;
 }
 
-int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q, void* dev_out,
-                     void* dev_workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!pool || !desc || !dev_q || !dev_out || !dev_workspace) return IC_ENULL;
-  int rc = check_batch(pool->cfg, desc, (desc->flags & IC_FLAG_TRUSTED) != 0);
-  if (rc != IC_OK) return rc;
-  if (misaligned(dev_q) || misaligned(dev_out) || ((uintptr_t)dev_workspace & 255u)) return IC_EALIGN;
-  PlanSizes ps;
-  plan_sizes(pool, desc, ps);
-  if (workspace_bytes < ps.total_bytes) return IC_ESIZE;
-
-  hipStream_t st = (hipStream_t)hip_stream;
+// Upload of the descriptor image of a planned batch into the workspace (through the pinned ring).
+static int upload_plan(ic_pool* pool, const ic_batch_desc* desc, const PlanSizes& ps, char* ws, hipStream_t st) {
   StagingSlot* slot = nullptr;
-  rc = acquire_slot(pool, ps.image_bytes, &slot);
+  const int rc = acquire_slot(pool, ps.image_bytes, &slot);
   if (rc != IC_OK) return rc;
   plan_fill(desc, ps, (char*)slot->host);
-  char* ws = (char*)dev_workspace;
   {
     ProfScope ps_(pool, IC_K_UPLOAD, st);
     if (launch_upload(ws, slot->host, ps.image_bytes, st) != hipSuccess) return IC_EHIP;
   }
   if (hipEventRecord(slot->ev, st) != hipSuccess) return IC_EHIP;
   slot->pending = true;
+  return IC_OK;
+}
 
+// The kernels of one attention call, for a descriptor image that is already in the workspace.
+static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, const void* dev_q, void* dev_out,
+                            char* ws, hipStream_t st) {
   const int D = pool->cfg.head_dim;
   if (pool->num_cus == 0) {
     int dev = 0, cus = 0;
@@ -483,7 +490,7 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
   p.n_row_items = ps.info.row_items;
   p.n_tile_items = ps.info.tile_items;
   p.n_merge_items = ps.info.merge_rows;
-  p.scale_log2e = desc->scale * 1.4426950408889634f;
+  p.scale_log2e = scale * 1.4426950408889634f;
   p.row_variant = pool->tune.row_variant;
   p.counters = (int32_t*)(ws + ps.off_ctr);
 
@@ -535,6 +542,64 @@ int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q
     ProfScope ps_(pool, IC_K_MERGE, st);
     if (launch_merge_kernel(p, D, st) != hipSuccess) return IC_EHIP;
   }
+  return IC_OK;
+}
+
+
+int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q, void* dev_out,
+                     void* dev_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!pool || !desc || !dev_q || !dev_out || !dev_workspace) return IC_ENULL;
+  int rc = check_batch(pool->cfg, desc, (desc->flags & IC_FLAG_TRUSTED) != 0);
+  if (rc != IC_OK) return rc;
+  if (misaligned(dev_q) || misaligned(dev_out) || ((uintptr_t)dev_workspace & 255u)) return IC_EALIGN;
+  PlanSizes ps;
+  plan_sizes(pool, desc, ps);
+  if (workspace_bytes < ps.total_bytes) return IC_ESIZE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* ws = (char*)dev_workspace;
+  if ((rc = upload_plan(pool, desc, ps, ws, st)) != IC_OK) return rc;
+  return launch_attention(pool, ps, desc->scale, dev_q, dev_out, ws, st);
+}
+
+int paged_attn_plan_create(ic_pool* pool, const ic_batch_desc* desc, void* dev_workspace, size_t workspace_bytes,
+                           void* hip_stream, ic_plan** out) {
+  if (!pool || !desc || !dev_workspace || !out) return IC_ENULL;
+  int rc = check_batch(pool->cfg, desc, (desc->flags & IC_FLAG_TRUSTED) != 0);
+  if (rc != IC_OK) return rc;
+  if ((uintptr_t)dev_workspace & 255u) return IC_EALIGN;
+  ic_plan* pl = new (std::nothrow) ic_plan();
+  if (!pl) return IC_ENOMEM;
+  plan_sizes(pool, desc, pl->ps);
+  if (workspace_bytes < pl->ps.total_bytes) {
+    delete pl;
+    return IC_ESIZE;
+  }
+  pl->cfg = pool->cfg;
+  pl->tune = pool->tune;
+  pl->scale = desc->scale;
+  pl->ws = (char*)dev_workspace;
+  if ((rc = upload_plan(pool, desc, pl->ps, pl->ws, (hipStream_t)hip_stream)) != IC_OK) {
+    delete pl;
+    return rc;
+  }
+  *out = pl;
+  return IC_OK;
+}
+
+int paged_attn_planned(ic_pool* pool, const ic_plan* plan, const void* dev_q, void* dev_out, void* hip_stream) {
+  if (!pool || !plan || !dev_q || !dev_out) return IC_ENULL;
+  const ic_pool_cfg &a = pool->cfg, &b = plan->cfg;
+  if (a.num_blocks != b.num_blocks || a.block_size != b.block_size || a.num_heads != b.num_heads ||
+      a.num_kv_heads != b.num_kv_heads || a.head_dim != b.head_dim || a.dtype != b.dtype || a.layout != b.layout)
+    return IC_EINVAL;  // the plan was made for another shape
+  if (std::memcmp(&pool->tune, &plan->tune, sizeof(ic_tuning)) != 0) return IC_EINVAL;  // or another launch plan
+  if (misaligned(dev_q) || misaligned(dev_out)) return IC_EALIGN;
+  return launch_attention(pool, plan->ps, plan->scale, dev_q, dev_out, plan->ws, (hipStream_t)hip_stream);
+}
+
+int paged_attn_plan_destroy(ic_plan* plan) {
+  if (!plan) return IC_ENULL;
+  delete plan;
   return IC_OK;
 }
 

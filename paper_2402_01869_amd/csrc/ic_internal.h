@@ -82,6 +82,24 @@ struct AttnParams {
   int32_t* counters;       // 16 work-queue counters, zero when the kernel starts
 };
 
+// Work-queue counters of the persistent kernels (16 ints at the head of the descriptor image):
+//   [0..7] tile queue of each XCD, [9] shared tile queue, [8] row queue, [12] / [13] workgroups of the
+//   row / tile kernel that have left.
+// A persistent kernel's workgroups leave through queue_leave: the last one out (every other has made
+// its final, failing pull by then) puts the kernel's counters back to zero, so that a descriptor
+// image already in device memory serves the next launch as it is.
+constexpr int kCtrRowQueue = 8, kCtrTileShared = 9, kCtrRowLeft = 12, kCtrTileLeft = 13;
+__device__ __forceinline__ void queue_leave(int32_t* counters, int first, int count, int extra, int left_slot) {
+  if (threadIdx.x == 0) {
+    const int gone = atomicAdd(&counters[left_slot], 1);
+    if (gone == (int)gridDim.x - 1) {
+      for (int i = 0; i < count; ++i) atomicExch(&counters[first + i], 0);
+      if (extra >= 0) atomicExch(&counters[extra], 0);
+      atomicExch(&counters[left_slot], 0);
+    }
+  }
+}
+
 // Launchers (defined next to their kernels).  Each returns a hipError_t.
 hipError_t launch_row_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_row_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st);

@@ -122,6 +122,51 @@ def test_random_batches_and_plans(seed):
     _check_batch(batch, 9100 + seed, tunings=tunings)
 
 
+@pytest.mark.parametrize("H,Hkv,D,tuning", [(5, 5, 128, dict()), (5, 5, 128, dict(serial_spans=1, decode_part_tokens=128)),
+                                            (4, 4, 256, dict()), (16, 2, 128, dict()), (3, 3, 64, dict(span_kernel=1)),
+                                            (8, 8, 64, dict(span_part_tokens=128, decode_part_tokens=64))])
+def test_plan_once_run_for_every_layer(H, Hkv, D, tuning):
+    """One plan, three layers (three pools of one shape, their own q), each layer run twice from the same
+    descriptor image: bit-identical to paged_attn_mixed on that layer, which the oracle checks.  The
+    persistent kernels' work queues must come back to zero by themselves between the runs."""
+    rng = np.random.default_rng(H + Hkv + D)
+    batch = W.assemble_batch(H, D, 16, 256, [700, 33, 300, 1, 129, 1000, 64], [200, 1, 300, 1, 128, 1, 1], rng,
+                             num_kv_heads=Hkv)
+    layers = []
+    for l in range(3):
+        pool_bits = W.randn_bf16(W.pool_shape(256, Hkv, 16, D), np.random.default_rng(100 + l))
+        W.poison_pool(pool_bits, batch)
+        q_bits = W.randn_bf16((batch.total_q_rows, H, D), np.random.default_rng(200 + l))
+        pool, keep = make_pool(pool_bits, H)
+        pool.set_tuning(**tuning)
+        layers.append((pool, keep, pool_bits, q_bits))
+    want0 = oracle.attn_batch(batch, layers[0][2], layers[0][3])
+    runners = [AttnRunner(pool, batch, q_bits) for pool, _, _, q_bits in layers]
+    ref = [r.run().copy() for r in runners]                       # paged_attn_mixed, layer by layer
+    assert max_abs_err(ref[0], want0) <= TOL
+    desc = runners[0].desc
+    ws = torch.empty(layers[0][0].workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    plan = layers[0][0].plan_create(desc, ws.data_ptr(), ws.numel())
+    for rep in range(2):
+        for l, (pool, _, _, _) in enumerate(layers):
+            r = runners[l]
+            r.out.fill_(0x7FFF)
+            pool.paged_attn_planned(plan, r.q.data_ptr(), r.out.data_ptr())
+            torch.cuda.synchronize()
+            assert np.array_equal(from_dev_bits(r.out), ref[l]), (rep, l)
+    # a pool of another shape, or with other launch knobs, cannot use the plan
+    other_bits = W.randn_bf16(W.pool_shape(128, Hkv, 16, D), rng)
+    other, keep2 = make_pool(other_bits, H)
+    r = runners[0]
+    assert other.paged_attn_planned(plan, r.q.data_ptr(), r.out.data_ptr(), check=False) == B.IC_EINVAL
+    layers[1][0].set_tuning(decode_part_tokens=192)
+    assert layers[1][0].paged_attn_planned(plan, r.q.data_ptr(), r.out.data_ptr(), check=False) == B.IC_EINVAL
+    plan.close()
+    other.close()
+    for pool, _, _, _ in layers:
+        pool.close()
+
+
 def test_caller_stream_and_back_to_back_calls():
     """Calls issued back to back on a caller's (non-default) stream, alternating two batches that share
     the pool's descriptor ring and side stream, give what each gives alone."""
