@@ -2,6 +2,7 @@
 // See include/infercept_hot.h for the contract of every entry point.
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -298,6 +299,21 @@ void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
 // ---------------------------------------------------------------------------------------
 // Runtime helpers
 // ---------------------------------------------------------------------------------------
+// The second stream of the side-by-side launch.  ONE per device for the whole process, shared by all
+// pools (a model has one pool per layer): a process gets few hardware queues (four by default), streams
+// are dealt onto them round-robin, and two streams on one queue run in order; a side stream per pool
+// would sooner or later share the caller's queue and silently serialise the two kernels.  Lives until
+// the process ends.
+hipStream_t shared_side_stream() {
+  static std::mutex mu;
+  static hipStream_t side[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!side[dev] && hipStreamCreateWithFlags(&side[dev], hipStreamNonBlocking) != hipSuccess) side[dev] = nullptr;
+  return side[dev];
+}
+
 int acquire_slot(ic_pool* pool, size_t bytes, StagingSlot** out) {
   StagingSlot& s = pool->slots[pool->next_slot];
   pool->next_slot = (pool->next_slot + 1) % kStagingSlots;
@@ -393,10 +409,7 @@ int kv_pool_destroy(ic_pool* pool) {
   }
   for (hipEvent_t e : pool->prof.ev) (void)hipEventDestroy(e);
   if (pool->dev_ids) (void)hipFree(pool->dev_ids);
-  if (pool->side) {
-    if (hipStreamSynchronize(pool->side) != hipSuccess) rc = IC_EHIP;
-    (void)hipStreamDestroy(pool->side);
-  }
+  if (pool->side && hipStreamSynchronize(pool->side) != hipSuccess) rc = IC_EHIP;  // shared: never destroyed
   if (pool->ev_fork) (void)hipEventDestroy(pool->ev_fork);
   if (pool->ev_join) (void)hipEventDestroy(pool->ev_join);
   delete pool;
@@ -505,7 +518,7 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
                       !ps.decode_as_group;
   if (beside) {
     if (!pool->side) {
-      if (hipStreamCreateWithFlags(&pool->side, hipStreamNonBlocking) != hipSuccess) return IC_EHIP;
+      if (!(pool->side = shared_side_stream())) return IC_EHIP;
       if (hipEventCreateWithFlags(&pool->ev_fork, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
       if (hipEventCreateWithFlags(&pool->ev_join, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
     }
