@@ -150,6 +150,10 @@ typedef struct ic_plan ic_plan;
 int paged_attn_plan_create(ic_pool* pool, const ic_batch_desc* desc, void* dev_workspace, size_t workspace_bytes,
                            void* hip_stream, ic_plan** out);
 int paged_attn_planned(ic_pool* pool, const ic_plan* plan, const void* dev_q, void* dev_out, void* hip_stream);
+/* kv_write_span from the same plan (the rows' destinations are part of the image).  IC_EDUP if the
+ * plan's descriptor was not trusted and two of its rows address one cache slot. */
+int kv_write_span_planned(ic_pool* pool, const ic_plan* plan, const void* dev_k_new, const void* dev_v_new,
+                          void* hip_stream);
 int paged_attn_plan_destroy(ic_plan* plan);
 
 /* Host-only validation of a descriptor against a pool shape (what paged_attn_mixed checks when

@@ -32,7 +32,7 @@ EXPORTS = (
     "ic_host_alloc", "ic_host_free", "ic_swap_limit_tokens", "ic_swap_schedule", "kv_write_span",
     "ic_tfwd_eval", "ic_waste_discard", "ic_waste_preserve", "ic_waste_swap", "ic_waste_chunked_discard",
     "ic_chunk_tokens", "ic_chunk_count", "ic_saturation_point", "ic_schedule_intercepted",
-    "paged_attn_plan_create", "paged_attn_planned", "paged_attn_plan_destroy",
+    "paged_attn_plan_create", "paged_attn_planned", "paged_attn_plan_destroy", "kv_write_span_planned",
 )
 IC_ACT_NONE, IC_ACT_PRESERVE, IC_ACT_DISCARD = 0, 1, 2
 IC_SWAP_OUT, IC_SWAP_IN = 0, 1
@@ -115,6 +115,7 @@ def lib():
         L.kv_write_span.argtypes = [vp, C.POINTER(BatchDesc), vp, vp, vp]
         L.paged_attn_plan_create.argtypes = [vp, C.POINTER(BatchDesc), vp, C.c_size_t, vp, C.POINTER(vp)]
         L.paged_attn_planned.argtypes = [vp, vp, vp, vp, vp]
+        L.kv_write_span_planned.argtypes = [vp, vp, vp, vp, vp]
         L.paged_attn_plan_destroy.argtypes = [vp]
         L.ic_check_batch.argtypes = [C.POINTER(PoolCfg), C.POINTER(BatchDesc)]
         L.ic_pool_set_tuning.argtypes = [vp, C.POINTER(Tuning)]
@@ -280,6 +281,12 @@ class KvPool:
         rc = lib().paged_attn_planned(self._h, plan._h, C.c_void_p(q_ptr), C.c_void_p(out_ptr), C.c_void_p(stream))
         if check and rc != IC_OK:
             raise InferceptError(rc, "paged_attn_planned")
+        return int(rc)
+
+    def kv_write_span_planned(self, plan: "AttnPlan", k_ptr: int, v_ptr: int, stream: int = 0, check: bool = True) -> int:
+        rc = lib().kv_write_span_planned(self._h, plan._h, C.c_void_p(k_ptr), C.c_void_p(v_ptr), C.c_void_p(stream))
+        if check and rc != IC_OK:
+            raise InferceptError(rc, "kv_write_span_planned")
         return int(rc)
 
     def kv_write_span(self, desc: HostDesc, k_ptr: int, v_ptr: int, stream: int = 0, check: bool = True) -> int:

@@ -122,6 +122,29 @@ int check_ids(const ic_pool_cfg& cfg, const int32_t* ids, int32_t n, bool distin
   return IC_OK;
 }
 
+// Destination of every query row's new K/V: block * block_size + slot (rows no sequence owns keep -1).
+void append_destinations(const ic_batch_desc* desc, int32_t* dst) {
+  for (int s = 0; s < desc->num_seqs; ++s) {
+    const int32_t* table = desc->block_tables + (int64_t)s * desc->max_blocks_per_seq;
+    const int t0 = desc->ctx_len[s] - desc->q_len[s];
+    for (int i = 0; i < desc->q_len[s]; ++i) {
+      const int t = t0 + i;
+      dst[desc->q_start[s] + i] = table[t / kBlockSize] * kBlockSize + t % kBlockSize;
+    }
+  }
+}
+
+// Two rows on one slot would make the result depend on the order of the writes.
+bool destinations_distinct(const ic_pool_cfg& cfg, const int32_t* dst, size_t rows) {
+  std::vector<uint8_t> seen((size_t)cfg.num_blocks * kBlockSize, 0);
+  for (size_t r = 0; r < rows; ++r) {
+    if (dst[r] < 0) continue;
+    if (seen[dst[r]]) return false;
+    seen[dst[r]] = 1;
+  }
+  return true;
+}
+
 // ---------------------------------------------------------------------------------------
 // Launch plan.  Sizes only (plan_sizes) or the filled descriptor image (plan_fill).
 // Device image layout (all sections 256-byte aligned, in this order):
@@ -135,7 +158,7 @@ struct PlanSizes {
   bool spans_as_rows;
   bool decode_as_tiles;                // grouped pools, span_kernel = 2: decode rows as one-row tile items
   bool decode_as_group;                // grouped pools: decode rows stay row items, run by the group kernel
-  size_t off_ctr, off_bt_off, off_bt_flat, off_row, off_tile, off_merge, image_bytes;
+  size_t off_ctr, off_bt_off, off_bt_flat, off_row, off_tile, off_merge, off_row_dst, image_bytes;
   size_t off_part_o, off_part_ml, total_bytes;
 };
 
@@ -149,6 +172,8 @@ struct ic_plan {
   ic_tuning tune;    // launch knobs it was made with
   float scale;
   char* ws;          // the caller's workspace: descriptor image + partial results
+  int32_t total_q_rows;
+  bool append_checked;  // the rows' cache slots were found distinct (or the descriptor was trusted)
 };
 
 namespace {
@@ -215,6 +240,7 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   ps.off_row = o;     o = align_up(o + sizeof(RowItem) * (size_t)in.row_items, 256);
   ps.off_tile = o;    o = align_up(o + sizeof(TileItem) * (size_t)in.tile_items, 256);
   ps.off_merge = o;   o = align_up(o + sizeof(MergeItem) * (size_t)in.merge_rows, 256);
+  ps.off_row_dst = o; o = align_up(o + sizeof(int32_t) * (size_t)d->total_q_rows, 256);  // for kv_write_span_planned
   ps.image_bytes = o;
   ps.off_part_o = o;  o = align_up(o + sizeof(float) * (size_t)in.partial_slots * H * D, 256);
   ps.off_part_ml = o; o = align_up(o + sizeof(float) * (size_t)in.partial_slots * H * 2, 256);
@@ -229,6 +255,11 @@ void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
   RowItem* rows = (RowItem*)(img + ps.off_row);
   TileItem* tiles = (TileItem*)(img + ps.off_tile);
   MergeItem* merges = (MergeItem*)(img + ps.off_merge);
+  {
+    int32_t* row_dst = (int32_t*)(img + ps.off_row_dst);
+    std::fill(row_dst, row_dst + (ps.image_bytes - ps.off_row_dst) / sizeof(int32_t), -1);
+    append_destinations(d, row_dst);
+  }
   int64_t nbt = 0;
   int nrow = 0, ntiles = 0, nmerge = 0, slot = 0;
   for (int s = 0; s < d->num_seqs; ++s) {
@@ -591,6 +622,13 @@ int paged_attn_plan_create(ic_pool* pool, const ic_batch_desc* desc, void* dev_w
   pl->tune = pool->tune;
   pl->scale = desc->scale;
   pl->ws = (char*)dev_workspace;
+  pl->total_q_rows = desc->total_q_rows;
+  pl->append_checked = true;
+  if (!(desc->flags & IC_FLAG_TRUSTED)) {
+    std::vector<int32_t> dst((size_t)desc->total_q_rows, -1);
+    append_destinations(desc, dst.data());
+    pl->append_checked = destinations_distinct(pool->cfg, dst.data(), dst.size());
+  }
   if ((rc = upload_plan(pool, desc, pl->ps, pl->ws, (hipStream_t)hip_stream)) != IC_OK) {
     delete pl;
     return rc;
@@ -608,6 +646,22 @@ int paged_attn_planned(ic_pool* pool, const ic_plan* plan, const void* dev_q, vo
   if (std::memcmp(&pool->tune, &plan->tune, sizeof(ic_tuning)) != 0) return IC_EINVAL;  // or another launch plan
   if (misaligned(dev_q) || misaligned(dev_out)) return IC_EALIGN;
   return launch_attention(pool, plan->ps, plan->scale, dev_q, dev_out, plan->ws, (hipStream_t)hip_stream);
+}
+
+int kv_write_span_planned(ic_pool* pool, const ic_plan* plan, const void* dev_k_new, const void* dev_v_new,
+                          void* hip_stream) {
+  if (!pool || !plan || !dev_k_new || !dev_v_new) return IC_ENULL;
+  const ic_pool_cfg &a = pool->cfg, &b = plan->cfg;
+  if (a.num_blocks != b.num_blocks || a.block_size != b.block_size || a.num_heads != b.num_heads ||
+      a.num_kv_heads != b.num_kv_heads || a.head_dim != b.head_dim || a.dtype != b.dtype || a.layout != b.layout)
+    return IC_EINVAL;
+  if (!plan->append_checked) return IC_EDUP;
+  if (misaligned(dev_k_new) || misaligned(dev_v_new)) return IC_EALIGN;
+  hipStream_t st = (hipStream_t)hip_stream;
+  ProfScope ps_(pool, IC_K_APPEND, st);
+  const hipError_t e = launch_append(pool->base, dev_k_new, dev_v_new, (const int32_t*)(plan->ws + plan->ps.off_row_dst),
+                                     plan->total_q_rows, a.num_kv_heads, a.head_dim, st);
+  return e == hipSuccess ? IC_OK : IC_EHIP;
 }
 
 int paged_attn_plan_destroy(ic_plan* plan) {
@@ -687,26 +741,11 @@ int kv_write_span(ic_pool* pool, const ic_batch_desc* desc, const void* dev_k_ne
   int rc = check_batch(pool->cfg, desc, trusted);
   if (rc != IC_OK) return rc;
   if (misaligned(dev_k_new) || misaligned(dev_v_new)) return IC_EALIGN;
-  // destination of every row: block * block_size + slot, or -1 for rows no sequence owns
   const size_t rows = (size_t)desc->total_q_rows;
   const size_t bytes = align_up(sizeof(int32_t) * rows, 16);
   std::vector<int32_t> dst(bytes / sizeof(int32_t), -1);
-  for (int s = 0; s < desc->num_seqs; ++s) {
-    const int32_t* table = desc->block_tables + (int64_t)s * desc->max_blocks_per_seq;
-    const int t0 = desc->ctx_len[s] - desc->q_len[s];
-    for (int i = 0; i < desc->q_len[s]; ++i) {
-      const int t = t0 + i;
-      dst[desc->q_start[s] + i] = table[t / kBlockSize] * kBlockSize + t % kBlockSize;
-    }
-  }
-  if (!trusted) {  // two rows on one slot would make the result depend on the order of the writes
-    std::vector<uint8_t> seen((size_t)pool->cfg.num_blocks * kBlockSize, 0);
-    for (size_t r = 0; r < rows; ++r) {
-      if (dst[r] < 0) continue;
-      if (seen[dst[r]]) return IC_EDUP;
-      seen[dst[r]] = 1;
-    }
-  }
+  append_destinations(desc, dst.data());
+  if (!trusted && !destinations_distinct(pool->cfg, dst.data(), rows)) return IC_EDUP;
   if ((rc = ensure_dev_ids(pool, bytes)) != IC_OK) return rc;
   StagingSlot* slot = nullptr;
   if ((rc = acquire_slot(pool, bytes, &slot)) != IC_OK) return rc;

@@ -74,6 +74,53 @@ def test_append_then_attention_is_one_iteration():
     pool.close()
 
 
+def test_planned_append_and_attention_over_layers():
+    """An iteration over three layers from one plan: kv_write_span_planned then paged_attn_planned per layer,
+    no descriptor traffic after the plan; caches and outputs equal the oracle's, layer by layer."""
+    H, D, L = 4, 128, 3
+    rng = np.random.default_rng(91)
+    batch = W.assemble_batch(H, D, 16, 200, [500, 300, 129, 1000, 64], [100, 300, 128, 1, 1], rng)
+    desc = B.HostDesc.from_batch(batch)
+    pools, tensors, wants, outs, qs, knews, vnews, want_pools = [], [], [], [], [], [], [], []
+    for l in range(L):
+        r = np.random.default_rng(300 + l)
+        start = W.randn_bf16(W.pool_shape(200, H, 16, D), r)
+        k_new, v_new = W.randn_bf16((batch.total_q_rows, H, D), r), W.randn_bf16((batch.total_q_rows, H, D), r)
+        q_bits = W.randn_bf16((batch.total_q_rows, H, D), r)
+        full = start.copy()
+        oracle.kv_append(full, batch.ctx_len, batch.q_len, batch.q_start, batch.block_tables, k_new, v_new)
+        want_pools.append(full)
+        wants.append(oracle.attn_batch(batch, full, q_bits))
+        pool, t = make_pool(start)
+        pools.append(pool); tensors.append(t)
+        qs.append(to_dev_bits(q_bits)); knews.append(to_dev_bits(k_new)); vnews.append(to_dev_bits(v_new))
+        outs.append(torch.full((batch.total_q_rows, H, D), 0x7FFF, dtype=torch.int16, device=DEV))
+    ws = torch.empty(pools[0].workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    plan = pools[0].plan_create(desc, ws.data_ptr(), ws.numel(), st.cuda_stream)
+    for l in range(L):
+        pools[l].kv_write_span_planned(plan, knews[l].data_ptr(), vnews[l].data_ptr(), st.cuda_stream)
+        pools[l].paged_attn_planned(plan, qs[l].data_ptr(), outs[l].data_ptr(), st.cuda_stream)
+    st.synchronize()
+    for l in range(L):
+        assert np.array_equal(from_dev_bits(tensors[l]), want_pools[l]), l
+        assert max_abs_err(from_dev_bits(outs[l]), wants[l]) <= 1e-2, l
+    plan.close()
+    # a plan whose (checked) descriptor has two rows on one slot refuses the append
+    s0, s1 = 3, 4
+    ctx = batch.ctx_len.copy(); ctx[s1] = ctx[s0]
+    bt = batch.block_tables.copy(); bt[s1] = bt[s0]
+    dup = B.HostDesc(ctx, batch.q_len, batch.q_start, bt, batch.scale, batch.total_q_rows)
+    ws2 = torch.empty(pools[0].workspace_bytes(dup), dtype=torch.uint8, device=DEV)
+    plan2 = pools[0].plan_create(dup, ws2.data_ptr(), ws2.numel())
+    assert pools[0].kv_write_span_planned(plan2, knews[0].data_ptr(), vnews[0].data_ptr(), check=False) == B.IC_EDUP
+    torch.cuda.synchronize()
+    plan2.close()
+    for p in pools:
+        p.close()
+
+
 def test_mixed_13b_shape_append_sampled():
     """13B-shaped mixed batch (4224 rows, H40 D128, pool of 65536 blocks): every written slot against
     the oracle run on the blocks the batch references, and a checksum over the rest of the pool."""
