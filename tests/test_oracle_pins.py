@@ -624,3 +624,16 @@ def test_gqa_rejects_heads_that_do_not_divide():
     q = W.randn_bf16((1, 4, 8), rng)
     with pytest.raises(oracle.OracleError):
         oracle.paged_attn(pool, [5], [1], [0], np.zeros((1, 1), dtype=np.int32), q, 1.0)
+
+
+def test_stored_oracle_values_have_not_moved():
+    """tests/golden/*.txt were written by tests/golden/make_golden.py from the oracle alone (the paper prints no
+    worked values for this path); an edit that changes the oracle's arithmetic must show up here."""
+    import importlib.util
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    for name, fn in mod.FILES.items():
+        assert open(os.path.join(here, name)).read() == fn(), name
