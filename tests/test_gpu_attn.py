@@ -167,6 +167,37 @@ def test_plan_once_run_for_every_layer(H, Hkv, D, tuning):
         pool.close()
 
 
+@pytest.mark.parametrize("H,Hkv", [(2, 2), (8, 2)])
+def test_very_long_contexts_and_gaps_in_the_row_space(H, Hkv):
+    """A 40000-token decode sequence (20 key partitions), a chunk on a 20000-token prefix, and query rows laid
+    out with gaps: rows no sequence owns must keep their bytes."""
+    D = 128
+    rng = np.random.default_rng(H * 3 + Hkv)
+    batch = W.assemble_batch(H, D, 16, 4096, [40000, 20300, 5], [1, 300, 1], rng, num_kv_heads=Hkv)
+    batch.q_start = np.array([7, 20, 400], dtype=np.int32)            # rows 0-6, 8-19, 320-399, 401.. are nobody's
+    rows = 410
+    pool_bits = W.randn_bf16(W.pool_shape(4096, Hkv, 16, D), rng)
+    W.poison_pool(pool_bits, batch)
+    q_bits = W.randn_bf16((rows, H, D), rng)
+    want = oracle.paged_attn(pool_bits, batch.ctx_len, batch.q_len, batch.q_start, batch.block_tables, q_bits,
+                             batch.scale, rows)
+    pool, keep = make_pool(pool_bits, H)
+    desc = B.HostDesc(batch.ctx_len, batch.q_len, batch.q_start, batch.block_tables, batch.scale, rows)
+    q_t = to_dev_bits(q_bits)
+    out_t = torch.full((rows, H, D), 0x1234, dtype=torch.int16, device=DEV)
+    ws = torch.empty(pool.workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    assert pool.plan_query(desc)["partial_slots"] > 0
+    pool.paged_attn_mixed(desc, q_t.data_ptr(), out_t.data_ptr(), ws.data_ptr(), ws.numel())
+    torch.cuda.synchronize()
+    out = from_dev_bits(out_t)
+    owned = np.zeros(rows, dtype=bool)
+    for s in range(batch.num_seqs):
+        owned[batch.q_start[s]:batch.q_start[s] + batch.q_len[s]] = True
+    assert (out[~owned] == 0x1234).all(), "rows outside every sequence were written"
+    assert np.abs(W.bf16_bits_to_f64(out[owned]) - want[owned]).max() <= TOL
+    pool.close()
+
+
 def test_caller_stream_and_back_to_back_calls():
     """Calls issued back to back on a caller's (non-default) stream, alternating two batches that share
     the pool's descriptor ring and side stream, give what each gives alone."""
