@@ -26,7 +26,8 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
 # default launch plan of these workloads.
 MEASURED_TRAFFIC_BYTES = {"mixed_13b/row": (2836506 * 2.0 + 4254) * 1024,
                           "gptj_decode/row": (660656 * 2.0 + 3278) * 1024,
-                          "gqa_70b/row": (537675 * 2.0 + 5144) * 1024}
+                          "gqa_70b/row": (537675 * 2.0 + 5144) * 1024,
+                          "long_ctx/tile": (6133628 * 2.0 + 262292) * 1024}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
 
@@ -43,7 +44,7 @@ def parse_args():
     ap.add_argument("--serial-spans", type=int, default=0)
     ap.add_argument("--row-launch", type=int, default=0)
     ap.add_argument("--row-slots", type=int, default=0)
-    ap.add_argument("--mode", default="hot_path", choices=["hot_path", "swap_pipeline", "saturation"],
+    ap.add_argument("--mode", default="hot_path", choices=["hot_path", "swap_pipeline", "saturation", "ceilings"],
                     help="hot_path: the step described above (default); swap_pipeline: the layer-pipelined "
                          "swap to pinned host memory, alone and behind the attention call; saturation: "
                          "T_fwd profile of the attention call against query tokens, saturation point, waste model")
@@ -251,6 +252,35 @@ def swap_pipeline_bench(args):
     print(json.dumps(result))
 
 
+def ceilings_bench(args):
+    """What an MFMA-only loop reaches on this GPU (ic_mfma_ceiling) with zero, one and random N(0,1) bf16 operands:
+    context for the tile kernel's fraction of the vendor peak."""
+    import torch
+    from paper_2402_01869_amd import binding as B
+    from paper_2402_01869_amd import workloads as W
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    sink = torch.empty(B.IC_CEILING_SINK_BYTES, dtype=torch.uint8, device=dev)
+    n16 = B.IC_CEILING_OPERAND_BYTES // 2
+    rng = np.random.default_rng(7)
+    sets = {"zeros": np.zeros(n16, dtype=np.uint16), "ones": np.full(n16, 0x3F80, dtype=np.uint16),
+            "random_normal": W.randn_bf16((n16,), rng)}
+    out = {}
+    for name, bits in sets.items():
+        ops = torch.from_numpy(bits.view(np.int16)).to(dev)
+        best = None
+        for _ in range(3):
+            rc, tf, ghz = B.mfma_ceiling(ops.data_ptr(), ops.numel() * 2, sink.data_ptr(), sink.numel(), 200000)
+            if rc != B.IC_OK:
+                raise RuntimeError(B.strerror(rc))
+            if best is None or tf > best[0]:
+                best = (tf, ghz)
+        out[name] = {"TFLOPs": round(best[0], 1), "shader_GHz": round(best[1], 3),
+                     "frac_vendor_peak": round(best[0] / MFMA_BF16_PEAK_TFLOPS, 4)}
+    print(json.dumps({"metric": "MFMA-only loop rate, v_mfma_f32_32x32x16_bf16 on register operands", "unit": "TFLOP/s",
+                      "n_gpus": 1, "vendor_peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS, "operands": out}))
+
+
 def saturation_bench(args):
     """Section 4.2 on this machine, attention only: time of one layer's attention call for the 13B-shaped
     decode batch plus a growing number of recomputation query tokens -> T_fwd profile, saturation
@@ -333,7 +363,8 @@ def main():
         sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
         from paper_2402_01869_amd import binding as B
         B.lib()
-        return swap_pipeline_bench(args) if args.mode == "swap_pipeline" else saturation_bench(args)
+        return {"swap_pipeline": swap_pipeline_bench, "saturation": saturation_bench,
+                "ceilings": ceilings_bench}[args.mode](args)
     import torch
     sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
     from paper_2402_01869_amd import binding as B
@@ -547,6 +578,21 @@ def main():
                                 if not (args.decode_only or args.decode_part or args.span_part or args.serial_spans)
                                 else None),
                     "bytes_per_launch": dom_bytes, "avg_launch_ms": round(avg_ms("row"), 5)}
+
+    # Workloads whose floor is the spans' matrix work (long_ctx, gqa_70b): the dominant kernel is the tile kernel,
+    # priced against the dense bf16 MFMA peak.
+    if (prof["tile"]["launches"] and span_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) > kv_bytes / (HBM_PEAK_GBPS * 1e9)
+            and (not prof["row"]["launches"] or avg_ms("tile") > avg_ms("row"))):
+        G = H // acfg.kv_heads
+        grouped = 2 <= G <= 32 and G & (G - 1) == 0 and args.span_kernel == 0
+        persist = prof["row"]["launches"] > 0 and not args.serial_spans and D <= 128 and not grouped
+        ach = span_flops / (avg_ms("tile") * 1e-3) / 1e12
+        roofline = {"kernel": "tile_persist_kernel" if persist else "tile_attn_kernel",
+                    "runs_beside": "row_persist_slim_kernel" if persist else None,
+                    "bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS * 1.0,
+                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(f"{args.workload}/tile"),
+                    "flops_per_launch": span_flops, "avg_launch_ms": round(avg_ms("tile"), 5)}
 
     result = {
         "metric": "mixed paged-attn KV-read GB/s (% HBM peak); swap pack/unpack GB/s",

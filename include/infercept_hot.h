@@ -354,6 +354,26 @@ typedef struct {
 int ic_prof_begin(ic_pool* pool, int32_t max_launches);
 int ic_prof_end(ic_pool* pool, ic_prof_stats* out);
 
+/* ------------------------------------------------------------------------------------------
+ * Measurement aid for roofline reports (not part of the method): the rate an MFMA-only loop reaches
+ * on this GPU with the caller's operand data.  256 workgroups of 8 waves each issue iters x 4
+ * back-to-back independent v_mfma_f32_32x32x16_bf16 on register operands taken from dev_operands
+ * (bf16 bit patterns; zeros, ones or random values, the caller chooses), with no memory traffic in
+ * the loop.  With random operands the chip's power limit lowers the shader clock, so the result is
+ * below the vendor peak; *shader_ghz is the average shader clock inside the loop (shader-clock
+ * ticks over 100 MHz real-time ticks of workgroup 0).
+ *   dev_operands  DEVICE, 16-byte aligned, >= IC_CEILING_OPERAND_BYTES, only read
+ *   dev_sink      DEVICE, 16-byte aligned, >= IC_CEILING_SINK_BYTES, overwritten (results the
+ *                 compiler must not drop, and the clock readings)
+ *   iters         1 .. 2^24
+ * Synchronous: launches on hip_stream and waits for it.  Errors: IC_ENULL, IC_EINVAL, IC_ESIZE,
+ * IC_EALIGN, IC_EHIP; nothing is launched on a validation error.
+ */
+#define IC_CEILING_OPERAND_BYTES ((size_t)1 << 20)
+#define IC_CEILING_SINK_BYTES ((size_t)256 * 512 * 4 + (size_t)256 * 16)
+int ic_mfma_ceiling(const void* dev_operands, size_t operand_bytes, void* dev_sink, size_t sink_bytes,
+                    int32_t iters, void* hip_stream, double* tflops, double* shader_ghz);
+
 #ifdef __cplusplus
 }
 #endif

@@ -33,7 +33,10 @@ EXPORTS = (
     "ic_tfwd_eval", "ic_waste_discard", "ic_waste_preserve", "ic_waste_swap", "ic_waste_chunked_discard",
     "ic_chunk_tokens", "ic_chunk_count", "ic_saturation_point", "ic_schedule_intercepted",
     "paged_attn_plan_create", "paged_attn_planned", "paged_attn_plan_destroy", "kv_write_span_planned",
+    "ic_mfma_ceiling",
 )
+IC_CEILING_OPERAND_BYTES = 1 << 20
+IC_CEILING_SINK_BYTES = 256 * 512 * 4 + 256 * 16
 IC_ACT_NONE, IC_ACT_PRESERVE, IC_ACT_DISCARD = 0, 1, 2
 IC_SWAP_OUT, IC_SWAP_IN = 0, 1
 
@@ -504,3 +507,11 @@ def schedule_intercepted(waste_preserve_, waste_chunkd, ctx_tokens, budget: int)
     rc = int(lib().ic_schedule_intercepted(n, wp.ctypes.data_as(f64p), wc.ctypes.data_as(f64p), ct.ctypes.data_as(i64p),
                                            int(budget), sw.ctypes.data_as(i64p), act.ctypes.data_as(C.POINTER(C.c_int32))))
     return rc, sw, act
+
+
+def mfma_ceiling(dev_operands: int, operand_bytes: int, dev_sink: int, sink_bytes: int, iters: int, stream: int = 0):
+    """ic_mfma_ceiling: returns (rc, tflops, shader_ghz)."""
+    tf, ghz = C.c_double(0.0), C.c_double(0.0)
+    rc = lib().ic_mfma_ceiling(C.c_void_p(dev_operands), C.c_size_t(operand_bytes), C.c_void_p(dev_sink),
+                               C.c_size_t(sink_bytes), C.c_int32(iters), C.c_void_p(stream), C.byref(tf), C.byref(ghz))
+    return rc, tf.value, ghz.value

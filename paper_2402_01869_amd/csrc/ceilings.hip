@@ -1,0 +1,82 @@
+// Measurement aid, not part of the method: what an MFMA-only loop reaches on this GPU with the caller's operand
+// data.  With realistic (random) operands the power limit lowers the shader clock well below the nominal one, so
+// this figure, not the vendor peak, is what a perfectly fed matrix pipe could deliver; reports price the tile
+// kernel against both.
+#include "ic_internal.h"
+
+namespace ic {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int kCeilBlocks = 256, kCeilThreads = 512;   // one 8-wave workgroup per CU
+constexpr size_t kCeilOperandBytes = 1u << 20;          // 65536 16-byte operands
+constexpr size_t kCeilSinkBytes = (size_t)kCeilBlocks * kCeilThreads * 4 + (size_t)kCeilBlocks * 16;
+
+__global__ __launch_bounds__(kCeilThreads, 2) void mfma_ceiling_kernel(const u32x4* operands, float* sink,
+                                                                       long long* clocks, int iters) {
+  const int tid = threadIdx.x + blockIdx.x * kCeilThreads;
+  u32x4 ra = operands[(tid * 2) & 0xffff], rb = operands[(tid * 2 + 1) & 0xffff];
+  const bf16x8 a = *(bf16x8*)&ra, b = *(bf16x8*)&rb;
+  f32x16 acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+  const long long c0 = clock64(), w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+  }
+  const long long c1 = clock64(), w1 = wall_clock64();
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[j][i];
+  sink[tid] = s;
+  if (threadIdx.x == 0) {
+    clocks[blockIdx.x * 2] = c1 - c0;       // shader clock ticks
+    clocks[blockIdx.x * 2 + 1] = w1 - w0;   // constant 100 MHz ticks
+  }
+}
+
+}  // namespace
+}  // namespace ic
+
+extern "C" int ic_mfma_ceiling(const void* dev_operands, size_t operand_bytes, void* dev_sink, size_t sink_bytes,
+                               int32_t iters, void* hip_stream, double* tflops, double* shader_ghz) {
+  using namespace ic;
+  if (!dev_operands || !dev_sink || !tflops || !shader_ghz) return IC_ENULL;
+  if (iters <= 0 || iters > (1 << 24)) return IC_EINVAL;
+  if (operand_bytes < kCeilOperandBytes || sink_bytes < kCeilSinkBytes) return IC_ESIZE;
+  if (((uintptr_t)dev_operands | (uintptr_t)dev_sink) & 15) return IC_EALIGN;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+    if (e0) (void)hipEventDestroy(e0);
+    return IC_EHIP;
+  }
+  long long* clocks = (long long*)((char*)dev_sink + (size_t)kCeilBlocks * kCeilThreads * 4);
+  int rc = IC_OK;
+  float ms = 0.f;
+  long long host_clk[2] = {0, 0};
+  if (hipEventRecord(e0, st) != hipSuccess) rc = IC_EHIP;
+  if (rc == IC_OK) {
+    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(kCeilBlocks), dim3(kCeilThreads), 0, st, (const u32x4*)dev_operands,
+                       (float*)dev_sink, clocks, (int)iters);
+    if (hipGetLastError() != hipSuccess || hipEventRecord(e1, st) != hipSuccess ||
+        hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess ||
+        hipMemcpy(host_clk, clocks, sizeof host_clk, hipMemcpyDeviceToHost) != hipSuccess)
+      rc = IC_EHIP;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc != IC_OK) return rc;
+  const double flops = (double)kCeilBlocks * (kCeilThreads / 64) * (double)iters * 4.0 * 2.0 * 32 * 32 * 16;
+  *tflops = ms > 0.f ? flops / ((double)ms * 1e-3) / 1e12 : 0.0;
+  *shader_ghz = host_clk[1] > 0 ? (double)host_clk[0] / (double)host_clk[1] * 0.1 : 0.0;
+  return IC_OK;
+}

@@ -289,7 +289,13 @@ __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& i
   float m = kNegBig, l = 0.f;
 
   const char* pool = (const char*)p.pool;
-  const int32_t* bt = p.bt_flat + p.bt_off[it.seq];
+  // The block table is read through the constant address space: its entries are wave-uniform and nothing
+  // writes them while the kernel runs, so they can come as scalar loads.  As vector loads they would be
+  // the youngest loads in flight whenever the next tile's addresses are needed, and waiting for them
+  // (loads return in order) would also wait for every K/V tile load issued before them, which cuts
+  // the prefetch distance from two tiles to one.
+  typedef __attribute__((address_space(4))) const int32_t const_i32;
+  const_i32* bt = (const_i32*)(p.bt_flat + p.bt_off[it.seq]);
   const int last_blk = (it.k_end - 1) / kBlockSize;  // last table entry this item may touch
   const int n_tiles = (it.k_end - it.k_begin + kTileK - 1) / kTileK;
   const float sc = p.scale_log2e;
@@ -309,26 +315,36 @@ __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& i
   // buffer that step t+1 will overwrite.  (Slipping the copies and loads between the MFMAs instead
   // of issuing them after the tile's arithmetic costs about 45 more registers and was slower.)
   // ids always holds the block ids of the tile the next fetch will read, loaded a step ahead.
+  // Every fetch is issued unconditionally; tiles past the item's end re-read its last block (tile_ids
+  // clamps to it) and are never staged.  Loads return in order and a wait names how many younger loads
+  // may stay in flight, so the compiler can let the newer register set's loads fly while the older
+  // set is copied to LDS only if that number is the same on every path through the loop.  With
+  // fetches skipped at the tail it is not, every copy waits for all loads, and the prefetch distance
+  // drops from two tiles to one.  For the same reason the two-set loop always runs whole pairs of
+  // steps; the odd one out does no arithmetic and no copy.
   constexpr int PFD = D <= 128 ? 2 : 1;
   constexpr int kBuf = tile_buf_elems<D>();
   Staging<D> st[PFD];
   int ids[4];
   tile_ids(0, ids);
   fetch_tile<D>(st[0], pool, ids, kvh, Hk, tid);
-  if (PFD == 2 && n_tiles > 1) {
+  if (PFD == 2) {
     tile_ids(1, ids);
     fetch_tile<D>(st[PFD - 1], pool, ids, kvh, Hk, tid);
   }
   stage_half<D>(st[0], 0, lds, lds + kTileK * G::kKStride, tid, it.k_end - it.k_begin);
   stage_half<D>(st[0], 1, lds, lds + kTileK * G::kKStride, tid, it.k_end - it.k_begin);
-  if (PFD < n_tiles) {
-    tile_ids(PFD, ids);
-    fetch_tile<D>(st[0], pool, ids, kvh, Hk, tid);
-    if (PFD + 1 < n_tiles) tile_ids(PFD + 1, ids);
-  }
+  tile_ids(PFD, ids);
+  fetch_tile<D>(st[0], pool, ids, kvh, Hk, tid);
+  tile_ids(PFD + 1, ids);
   __syncthreads();
 
-  const bool feed_first = TW<D>::kWaves == 8 && (w & 4) != 0;  // wave-uniform
+  // Waves w and w + 4 share a SIMD.  The first does its arithmetic, then its copy to LDS; the second
+  // the other way round, so that between two barriers one wave of a SIMD is in the matrix and vector
+  // pipes while the other waits on memory and LDS writes, instead of both doing the same thing at
+  // the same time.  The loads that refill the register set come last for both: with no load between
+  // the two possible places of the copy, the number of younger loads in flight is the same at both.
+  const bool copy_first = TW<D>::kWaves == 8 && (w & 4) != 0;  // wave-uniform
   // step t with its register set fixed at compile time (RS = (t + 1) % PFD holds tile t + 1)
   auto step = [&](int t, Staging<D>& sreg) {
     const int kt = it.k_begin + t * kTileK;
@@ -336,31 +352,25 @@ __device__ __forceinline__ void tile_body(const AttnParams& p, const TileItem& i
     const uint16_t* vs = ks + kTileK * G::kKStride;
     uint16_t* nks = lds + ((t + 1) & 1) * kBuf;
     uint16_t* nvs = nks + kTileK * G::kKStride;
-    // Waves w and w + 4 share a SIMD.  The first does its arithmetic, then its copy and loads; the
-    // second the other way round, so that between two barriers one wave of a SIMD is in the matrix
-    // and vector pipes while the other waits on memory and LDS writes, instead of both doing the
-    // same thing at the same time.
-    auto feed = [&]() {
+    auto copy = [&]() {
       if (t + 1 < n_tiles) {
         const int n_valid_next = it.k_end - (kt + kTileK);
         stage_half<D>(sreg, 0, nks, nvs, tid, n_valid_next);
         stage_half<D>(sreg, 1, nks, nvs, tid, n_valid_next);
       }
-      if (t + 1 + PFD < n_tiles) {
-        fetch_tile<D>(sreg, pool, ids, kvh, Hk, tid);
-        if (t + 2 + PFD < n_tiles) tile_ids(t + 2 + PFD, ids);
-      }
     };
-    if (feed_first) feed();
-    if (kt <= wave_pos_hi)  // otherwise every key of the tile is in this wave's future
+    if (copy_first) copy();
+    if (t < n_tiles && kt <= wave_pos_hi)  // otherwise every key of the tile is in this wave's future
       wave_step<D>(ks, vs, qreg, acc_o, m, l, kt, pos, col, hl, sc, kt + kTileK - 1 > wave_pos_lo);
-    if (!feed_first) feed();
+    if (!copy_first) copy();
+    fetch_tile<D>(sreg, pool, ids, kvh, Hk, tid);
+    tile_ids(t + 2 + PFD, ids);
     __syncthreads();
   };
   if constexpr (PFD == 2) {
     for (int t = 0; t < n_tiles; t += 2) {
       step(t, st[1]);
-      if (t + 1 < n_tiles) step(t + 1, st[0]);
+      step(t + 1, st[0]);
     }
   } else {
     for (int t = 0; t < n_tiles; ++t) step(t, st[0]);

@@ -6,7 +6,7 @@ import torch
 import oracle
 from paper_2402_01869_amd import binding as B
 from paper_2402_01869_amd import workloads as W
-from gpu_common import DEV
+from gpu_common import DEV, to_dev_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -89,3 +89,19 @@ def test_errors_leave_memory_untouched():
     assert (staging.cpu().numpy() == 7).all()
     assert np.array_equal(pool_t.cpu().numpy(), pool_host)
     pool.close()
+
+
+@pytest.mark.gpu
+def test_mfma_ceiling_reports_a_rate_and_a_clock():
+    """The measurement aid runs and returns plausible figures: a rate below the vendor peak (plus timer slack) and a
+    shader clock between 0.3 and 2.6 GHz."""
+    rng = np.random.default_rng(3)
+    n16 = B.IC_CEILING_OPERAND_BYTES // 2
+    sink = torch.empty(B.IC_CEILING_SINK_BYTES, dtype=torch.uint8, device=DEV)
+    for name, bits in (("zeros", np.zeros(n16, dtype=np.uint16)), ("random", W.randn_bf16((n16,), rng))):
+        ops = to_dev_bits(bits)
+        for _ in range(2):   # the first call after an idle gap runs while the clocks ramp
+            rc, tf, ghz = B.mfma_ceiling(ops.data_ptr(), ops.numel() * 2, sink.data_ptr(), sink.numel(), 20000)
+            assert rc == B.IC_OK
+        print(name, tf, ghz, flush=True)
+        assert 50.0 < tf < 2600.0 and 0.3 < ghz < 2.6, (name, tf, ghz)

@@ -336,3 +336,14 @@ def test_kernel_register_budgets():
         assert find("tile_attn_kernel", dim)["VGPRs Spill"] == 0
     for dim in (64, 128):
         assert find("tile_persist_kernel", dim)["VGPRs Spill"] == 0
+
+
+def test_mfma_ceiling_rejects_bad_arguments_before_any_launch():
+    """Validation happens on the host: these calls return before touching the GPU (none is present here)."""
+    ok_ops, ok_sink = 0x1000, 0x2000   # never dereferenced: every call below fails validation first
+    assert B.mfma_ceiling(0, B.IC_CEILING_OPERAND_BYTES, ok_sink, B.IC_CEILING_SINK_BYTES, 10)[0] == B.IC_ENULL
+    assert B.mfma_ceiling(ok_ops, B.IC_CEILING_OPERAND_BYTES, 0, B.IC_CEILING_SINK_BYTES, 10)[0] == B.IC_ENULL
+    assert B.mfma_ceiling(ok_ops, B.IC_CEILING_OPERAND_BYTES, ok_sink, B.IC_CEILING_SINK_BYTES, 0)[0] == B.IC_EINVAL
+    assert B.mfma_ceiling(ok_ops, B.IC_CEILING_OPERAND_BYTES - 1, ok_sink, B.IC_CEILING_SINK_BYTES, 10)[0] == B.IC_ESIZE
+    assert B.mfma_ceiling(ok_ops, B.IC_CEILING_OPERAND_BYTES, ok_sink, B.IC_CEILING_SINK_BYTES - 1, 10)[0] == B.IC_ESIZE
+    assert B.mfma_ceiling(ok_ops + 8, B.IC_CEILING_OPERAND_BYTES, ok_sink, B.IC_CEILING_SINK_BYTES, 10)[0] == B.IC_EALIGN
