@@ -548,10 +548,10 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
   const bool beside = p.n_tile_items > 0 && p.n_row_items > 0 && !pool->tune.serial_spans && D <= 128 &&
                       !ps.decode_as_group;
   if (beside) {
-    if (!pool->side) {
+    if (!pool->side) {  // the stream is assigned last: a half-made set is retried by the next call
+      if (!pool->ev_fork && hipEventCreateWithFlags(&pool->ev_fork, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
+      if (!pool->ev_join && hipEventCreateWithFlags(&pool->ev_join, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
       if (!(pool->side = shared_side_stream())) return IC_EHIP;
-      if (hipEventCreateWithFlags(&pool->ev_fork, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
-      if (hipEventCreateWithFlags(&pool->ev_join, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
     }
     if (hipEventRecord(pool->ev_fork, st) != hipSuccess) return IC_EHIP;
     if (hipStreamWaitEvent(pool->side, pool->ev_fork, 0) != hipSuccess) return IC_EHIP;

@@ -15,7 +15,9 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-2   # bf16 output, fp32 accumulation (the stated bar for this path)
 
 
-def _check_batch(batch, seed, tunings=((0, 0, 0),), tol=TOL):
+def _check_batch(batch, seed, tunings=((0, 0, 0),), tol=TOL, grid_slack=False):
+    """grid_slack: where |expected| >= 4 the bf16 grid itself is coarser than the bar (half an ulp is 1.56e-2 in
+    [4, 8)), so such elements are allowed half an ulp of the expected value plus 2e-3 instead."""
     pool_bits, q_bits = W.make_host_inputs(batch, seed, poison_unused=True)
     want = oracle.attn_batch(batch, pool_bits, q_bits)
     pool, keep = make_pool(pool_bits, batch.num_heads)
@@ -30,7 +32,13 @@ def _check_batch(batch, seed, tunings=((0, 0, 0),), tol=TOL):
         assert np.isfinite(W.bf16_bits_to_f64(out)).all(), tn
         e = max_abs_err(out, want)
         errs.append(e)
-        assert e <= tol, (tn, e)
+        if grid_slack:
+            err = np.abs(W.bf16_bits_to_f64(out) - want)
+            big = np.abs(want) >= 4.0
+            assert (err[~big] <= tol).all(), (tn, float(err[~big].max()))
+            assert (err[big] <= np.abs(want[big]) * 2.0 ** -8 + 2e-3).all(), (tn, float(err[big].max()))
+        else:
+            assert e <= tol, (tn, e)
         out2 = r.run()
         assert np.array_equal(out, out2), "not deterministic run to run"
     pool.close()
@@ -196,6 +204,39 @@ def test_very_long_contexts_and_gaps_in_the_row_space(H, Hkv):
     assert (out[~owned] == 0x1234).all(), "rows outside every sequence were written"
     assert np.abs(W.bf16_bits_to_f64(out[owned]) - want[owned]).max() <= TOL
     pool.close()
+
+
+@pytest.mark.parametrize("H,Hkv", [(4, 4), (8, 2)])
+def test_sequences_that_share_prefix_blocks(H, Hkv):
+    """Block tables of different sequences may name the same blocks (a shared prompt prefix is read-only here): three
+    sequences start with the same 37 blocks, then go their own way; one decodes, two recompute chunks."""
+    D = 128
+    rng = np.random.default_rng(11 * H + Hkv)
+    batch = W.assemble_batch(H, D, 16, 512, [700, 900, 650, 90], [1, 140, 58, 1], rng, num_kv_heads=Hkv)
+    shared = batch.block_tables[0, :37].copy()
+    batch.block_tables[1, :37] = shared
+    batch.block_tables[2, :37] = shared
+    pool_bits = W.randn_bf16(W.pool_shape(512, Hkv, 16, D), rng)
+    q_bits = W.randn_bf16((batch.total_q_rows, H, D), rng)
+    want = oracle.attn_batch(batch, pool_bits, q_bits)
+    pool, keep = make_pool(pool_bits, H)
+    for tn in ((0, 0, 0), (128, 128, 0), (0, 0, 1)):
+        pool.set_tuning(*tn)
+        out = AttnRunner(pool, batch, q_bits).run()
+        assert max_abs_err(out, want) <= TOL, tn
+    pool.close()
+
+
+def test_wide_batch_of_short_decode_sequences():
+    """3000 decode sequences with contexts of 1 to 40 tokens: thousands of one-block work items, most of them a
+    partial block; the persistent kernels' queues are far longer than their workgroup counts.  A context of one or
+    two tokens returns (nearly) a value row itself, and among 1.5 million N(0,1) values some exceed 4, where bf16
+    cannot hold 1e-2: those elements get the grid's own half ulp."""
+    H, D = 8, 64
+    rng = np.random.default_rng(2024)
+    ctx = rng.integers(1, 41, size=3000).tolist()
+    batch = W.assemble_batch(H, D, 16, 9000, ctx, [1] * 3000, rng)
+    _check_batch(batch, 4242, tunings=((0, 0, 0), dict(row_launch=1), dict(row_launch=3)), grid_slack=True)
 
 
 def test_caller_stream_and_back_to_back_calls():
