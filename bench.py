@@ -22,11 +22,13 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
 # command, scaled by the pack kernel's known 640 000 KiB (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 on this GPU);
 # figures and commands in profiles/row_and_tile_persist_kernels_mixed_13b.md,
-# profiles/row_persist_kernel_gptj_decode.md and profiles/group_and_tile_kernels_gqa_70b.md.  Only valid for the
+# profiles/row_persist_kernel_gptj_decode.md, profiles/group_and_tile_kernels_gqa_70b.md and
+# profiles/tile_persist_kernel_long_ctx.md.  Only valid for the
 # default launch plan of these workloads.
-MEASURED_TRAFFIC_BYTES = {"mixed_13b/row": (2836506 * 2.0 + 4254) * 1024,
+MEASURED_TRAFFIC_BYTES = {"mixed_13b/row": (2837644 * 2.0 + 4263) * 1024,
                           "gptj_decode/row": (660656 * 2.0 + 3278) * 1024,
                           "gqa_70b/row": (537675 * 2.0 + 5144) * 1024,
+                          "gqa_70b/tile": (84887 * 2.0 + 65536) * 1024,
                           "long_ctx/tile": (6133628 * 2.0 + 262292) * 1024}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
