@@ -191,6 +191,35 @@ typedef struct {
 } ic_plan_info;
 int ic_plan_query(const ic_pool* pool, const ic_batch_desc* desc, ic_plan_info* out);
 
+/* Host-only inspection of the launch plan, so that the planner can be tested without a GPU: writes
+ * into host_image the descriptor image paged_attn_mixed would upload for this batch under the
+ * pool's current tuning, and describes its layout.  All sections are int32 arrays at the given byte
+ * offsets: counters[16] (zero) | bt_off[num_seqs] | bt_flat[table_entries] (the sequences' block
+ * ids, back to back) | row items | tile items | merge items | row_dst[total_q_rows].
+ *   row item   (8 x int32): seq, qrow, k_begin, k_end, slot (-1: whole row, direct output), 0, 0, 0
+ *              one query row against keys [k_begin, k_end) of its sequence, all heads
+ *   tile item  (8 x int32): seq, qrow0, n_rows, pos0, k_begin, k_end, slot0 (-1: direct), nparts
+ *              n_rows consecutive query rows from qrow0, the first at position pos0, against keys
+ *              [k_begin, k_end) cut at each row's own position; partial slot of row r: slot0 + r * nparts
+ *   merge item (4 x int32): qrow, slot0, nparts, 0   (the row's partial slots are slot0 .. slot0 + nparts - 1)
+ *   row_dst    cache slot (block * block_size + slot in block) kv_write_span writes each query row's
+ *              K/V to, -1 for rows no sequence owns
+ * host_image may be NULL (layout only); otherwise host_bytes >= the image size (IC_ESIZE).  The
+ * descriptor is validated in full.  Touches no GPU state.
+ */
+typedef struct {
+  int64_t image_bytes;
+  int64_t off_counters, off_bt_off, off_bt_flat, off_row_items, off_tile_items, off_merge_items, off_row_dst;
+  int32_t row_part_tokens;   /* keys per row item                                             */
+  int32_t span_part_tokens;  /* keys per tile item (2^30: spans are not split)                */
+  int32_t tile_query_rows;   /* query rows per tile item                                      */
+  int32_t tile_head_shift;   /* log2 of the query heads one tile workgroup serves             */
+  int32_t n_row_items, n_tile_items, n_merge_items;
+  int32_t reserved;
+} ic_plan_layout;
+int ic_plan_image(const ic_pool* pool, const ic_batch_desc* desc, void* host_image, size_t host_bytes,
+                  ic_plan_layout* out);
+
 /* ------------------------------------------------------------------------------------------
  * Swap of scattered blocks (Section 3.2, swap-based approach: a paged context is scattered over
  * many discontinuous regions, and moving it with one launch per region is launch-bound;

@@ -33,7 +33,7 @@ EXPORTS = (
     "ic_tfwd_eval", "ic_waste_discard", "ic_waste_preserve", "ic_waste_swap", "ic_waste_chunked_discard",
     "ic_chunk_tokens", "ic_chunk_count", "ic_saturation_point", "ic_schedule_intercepted",
     "paged_attn_plan_create", "paged_attn_planned", "paged_attn_plan_destroy", "kv_write_span_planned",
-    "ic_mfma_ceiling",
+    "ic_mfma_ceiling", "ic_plan_image",
 )
 IC_CEILING_OPERAND_BYTES = 1 << 20
 IC_CEILING_SINK_BYTES = 256 * 512 * 4 + 256 * 16
@@ -67,6 +67,13 @@ class PlanInfo(C.Structure):
     _fields_ = [("decode_rows", C.c_int32), ("span_rows", C.c_int32), ("row_items", C.c_int32),
                 ("tile_items", C.c_int32), ("partial_slots", C.c_int32), ("merge_rows", C.c_int32),
                 ("table_entries", C.c_int64)]
+
+
+class PlanLayout(C.Structure):
+    _fields_ = ([(n, C.c_int64) for n in ("image_bytes", "off_counters", "off_bt_off", "off_bt_flat", "off_row_items",
+                                          "off_tile_items", "off_merge_items", "off_row_dst")] +
+                [(n, C.c_int32) for n in ("row_part_tokens", "span_part_tokens", "tile_query_rows", "tile_head_shift",
+                                          "n_row_items", "n_tile_items", "n_merge_items", "reserved")])
 
 
 class ProfStats(C.Structure):
@@ -260,6 +267,31 @@ class KvPool:
         if rc != IC_OK:
             raise InferceptError(rc, "ic_plan_query")
         return {n: int(getattr(info, n)) for n, _ in PlanInfo._fields_}
+
+    def plan_image(self, desc: HostDesc) -> dict:
+        """ic_plan_image: the launch plan as numpy arrays (host only, no GPU): layout fields plus `bt_off`, `bt_flat`,
+        `row_items` [n][8], `tile_items` [n][8], `merge_items` [n][4], `row_dst`, `counters`."""
+        lay = PlanLayout()
+        rc = lib().ic_plan_image(self._h, C.byref(desc.struct), None, C.c_size_t(0), C.byref(lay))
+        if rc != IC_OK:
+            raise InferceptError(rc, "ic_plan_image")
+        img = np.zeros(int(lay.image_bytes) // 4, dtype=np.int32)
+        rc = lib().ic_plan_image(self._h, C.byref(desc.struct), img.ctypes.data_as(C.c_void_p),
+                                 C.c_size_t(img.nbytes), C.byref(lay))
+        if rc != IC_OK:
+            raise InferceptError(rc, "ic_plan_image")
+        out = {n: int(getattr(lay, n)) for n, _ in PlanLayout._fields_ if n != "reserved"}
+        info = self.plan_query(desc)
+        sec = lambda off, count: img[off // 4: off // 4 + count]
+        out["counters"] = sec(out["off_counters"], 16)
+        out["bt_off"] = sec(out["off_bt_off"], int(desc.struct.num_seqs))
+        out["bt_flat"] = sec(out["off_bt_flat"], info["table_entries"])
+        out["row_items"] = sec(out["off_row_items"], 8 * out["n_row_items"]).reshape(-1, 8)
+        out["tile_items"] = sec(out["off_tile_items"], 8 * out["n_tile_items"]).reshape(-1, 8)
+        out["merge_items"] = sec(out["off_merge_items"], 4 * out["n_merge_items"]).reshape(-1, 4)
+        out["row_dst"] = sec(out["off_row_dst"], int(desc.struct.total_q_rows))
+        out["partial_slots"] = info["partial_slots"]
+        return out
 
     def workspace_bytes(self, desc: HostDesc) -> int:
         return int(lib().paged_attn_mixed_workspace_bytes(self._h, C.byref(desc.struct)))

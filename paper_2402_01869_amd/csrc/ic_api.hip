@@ -482,6 +482,37 @@ int ic_plan_query(const ic_pool* pool, const ic_batch_desc* desc, ic_plan_info* 
   return IC_OK;
 }
 
+int ic_plan_image(const ic_pool* pool, const ic_batch_desc* desc, void* host_image, size_t host_bytes,
+                  ic_plan_layout* out) {
+  if (!pool || !desc || !out) return IC_ENULL;
+  const int rc = check_batch(pool->cfg, desc, false);
+  if (rc != IC_OK) return rc;
+  PlanSizes ps;
+  plan_sizes(pool, desc, ps);
+  std::memset(out, 0, sizeof *out);
+  out->image_bytes = (int64_t)ps.image_bytes;
+  out->off_counters = (int64_t)ps.off_ctr;
+  out->off_bt_off = (int64_t)ps.off_bt_off;
+  out->off_bt_flat = (int64_t)ps.off_bt_flat;
+  out->off_row_items = (int64_t)ps.off_row;
+  out->off_tile_items = (int64_t)ps.off_tile;
+  out->off_merge_items = (int64_t)ps.off_merge;
+  out->off_row_dst = (int64_t)ps.off_row_dst;
+  out->row_part_tokens = ps.row_part;
+  out->span_part_tokens = ps.span_part;
+  out->tile_query_rows = ps.tile_rows;
+  out->tile_head_shift = ps.tile_g_shift;
+  out->n_row_items = ps.info.row_items;
+  out->n_tile_items = ps.info.tile_items;
+  out->n_merge_items = ps.info.merge_rows;
+  if (host_image) {
+    if (host_bytes < ps.image_bytes) return IC_ESIZE;
+    std::memset(host_image, 0, ps.image_bytes);
+    plan_fill(desc, ps, (char*)host_image);
+  }
+  return IC_OK;
+}
+
 size_t paged_attn_mixed_workspace_bytes(const ic_pool* pool, const ic_batch_desc* desc) {
   if (!pool || !desc) return 0;
   if (check_batch(pool->cfg, desc, true) != IC_OK) return 0;

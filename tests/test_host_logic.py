@@ -347,3 +347,94 @@ def test_mfma_ceiling_rejects_bad_arguments_before_any_launch():
     assert B.mfma_ceiling(ok_ops, B.IC_CEILING_OPERAND_BYTES - 1, ok_sink, B.IC_CEILING_SINK_BYTES, 10)[0] == B.IC_ESIZE
     assert B.mfma_ceiling(ok_ops, B.IC_CEILING_OPERAND_BYTES, ok_sink, B.IC_CEILING_SINK_BYTES - 1, 10)[0] == B.IC_ESIZE
     assert B.mfma_ceiling(ok_ops + 8, B.IC_CEILING_OPERAND_BYTES, ok_sink, B.IC_CEILING_SINK_BYTES, 10)[0] == B.IC_EALIGN
+
+
+def _check_plan_covers_every_row_once(pool, batch, desc):
+    """Every (query row, visible key) pair is handled by exactly one work item; partial slots are distinct and every
+    split row has a merge item naming them; tables, row destinations and alignment are as the kernels assume."""
+    P = pool.plan_image(desc)
+    assert not P["counters"].any()
+    # compact block tables
+    off = 0
+    for s in range(batch.num_seqs):
+        nb = (int(batch.ctx_len[s]) + 15) // 16
+        assert P["bt_off"][s] == off
+        assert np.array_equal(P["bt_flat"][off:off + nb], batch.block_tables[s, :nb])
+        off += nb
+    rows = int(desc.struct.total_q_rows)
+    klen = np.zeros(rows, dtype=np.int64)          # keys visible to each query row; 0 = nobody's row
+    want_dst = np.full(rows, -1, dtype=np.int64)
+    for s in range(batch.num_seqs):
+        c, n, r0 = int(batch.ctx_len[s]), int(batch.q_len[s]), int(batch.q_start[s])
+        for i in range(n):
+            t = c - n + i
+            klen[r0 + i] = t + 1
+            want_dst[r0 + i] = int(batch.block_tables[s, t // 16]) * 16 + t % 16
+    assert np.array_equal(P["row_dst"], want_dst)
+    ranges = [[] for _ in range(rows)]             # per row: (k_begin, k_end_visible, slot)
+    row_of_seq = {}
+    for seq, qrow, kb, ke, slot, p0, p1, p2 in P["row_items"].tolist():
+        assert kb % 16 == 0 and 0 <= kb < ke <= klen[qrow] and ke - kb <= P["row_part_tokens"] and p0 == p1 == p2 == 0
+        assert batch.q_start[seq] <= qrow < batch.q_start[seq] + batch.q_len[seq]
+        ranges[qrow].append((kb, ke, slot))
+    for seq, qrow0, n_rows, pos0, kb, ke, slot0, nparts in P["tile_items"].tolist():
+        assert kb % 64 == 0 and 1 <= n_rows <= P["tile_query_rows"] and nparts >= 1
+        assert pos0 == int(batch.ctx_len[seq] - batch.q_len[seq]) + (qrow0 - int(batch.q_start[seq]))
+        part = P["row_part_tokens"] if batch.q_len[seq] == 1 else P["span_part_tokens"]   # decode rows as one-row tiles
+        assert kb < ke <= pos0 + n_rows and ke - kb <= part
+        for r in range(n_rows):
+            vis_end = min(ke, pos0 + r + 1)
+            # a row whose position lies before this partition has nothing to do in it, but still owns a slot there
+            ranges[qrow0 + r].append((kb, max(vis_end, kb), -1 if slot0 < 0 else slot0 + r * nparts))
+    merges = {int(q): (int(s0), int(np_)) for q, s0, np_, pad in P["merge_items"].tolist()}
+    assert len(merges) == P["n_merge_items"]
+    seen_slots = set()
+    for r in range(rows):
+        if klen[r] == 0:
+            assert not ranges[r]
+            continue
+        parts = sorted(ranges[r])
+        assert parts[0][0] == 0
+        end = 0
+        for kb, ke, slot in parts:
+            if ke == kb:
+                assert kb >= klen[r], (r, parts)   # an empty partition lies wholly beyond the row's position
+                continue
+            assert kb == end, (r, parts)           # contiguous, no overlap
+            end = ke
+        assert end == klen[r], (r, parts, klen[r])
+        if len(parts) == 1:
+            assert parts[0][2] == -1 and r not in merges
+        else:
+            slots = sorted(p[2] for p in parts)
+            s0, np_ = merges[r]
+            assert slots == list(range(s0, s0 + np_)), (r, slots, merges[r])
+            assert not (seen_slots & set(slots))
+            seen_slots |= set(slots)
+    assert seen_slots == set(range(P["partial_slots"]))
+
+
+@pytest.mark.parametrize("H,Hkv,D", [(4, 4, 64), (5, 5, 128), (2, 2, 256), (8, 2, 128), (64, 8, 128), (6, 2, 64)])
+def test_launch_plan_covers_every_row_and_key_exactly_once(H, Hkv, D):
+    """ic_plan_image on random batches and tunings (host only): decode rows and spans, split and unsplit, spans as
+    rows or tiles, grouped pools with decode rows as group items or one-row tiles, gaps in the row space."""
+    rng = np.random.default_rng(1000 * H + 10 * Hkv + D)
+    for trial in range(6):
+        n_seq = int(rng.integers(1, 9))
+        ctx = rng.integers(1, 1500, size=n_seq).tolist()
+        qlen = [1 if rng.random() < 0.5 else int(rng.integers(1, c + 1)) for c in ctx]
+        if trial == 0:
+            ctx, qlen = [700, 5000, 64, 1], [300, 1, 64, 1]
+        batch = W.assemble_batch(H, D, 16, 2048, ctx, qlen, rng, num_kv_heads=Hkv)
+        total = batch.total_q_rows
+        if trial % 2:   # leave rows nobody owns between the sequences
+            batch.q_start = (batch.q_start + 3 * np.arange(batch.num_seqs)).astype(np.int32)
+            total += 3 * batch.num_seqs + 5
+        cfg = B.make_cfg(2048, H, D, num_kv_heads=Hkv)
+        pool = B.KvPool(cfg, 0x10000, 2048 * 16 * 2 * Hkv * D * 2)   # the base address is never dereferenced here
+        desc = B.HostDesc(batch.ctx_len, batch.q_len, batch.q_start, batch.block_tables, batch.scale, total)
+        for tn in (dict(), dict(decode_part_tokens=64, span_part_tokens=64), dict(span_kernel=1, decode_part_tokens=128),
+                   dict(span_kernel=2, decode_part_tokens=256, span_part_tokens=128), dict(span_part_tokens=1 << 20)):
+            pool.set_tuning(**tn)
+            _check_plan_covers_every_row_once(pool, batch, desc)
+        pool.close()
