@@ -84,22 +84,24 @@ struct ic_swapper {
 
 namespace {
 
+// Every object is created only if it is still missing, so a call that failed half-way is completed,
+// not repeated, by the next one.
 int init_runtime(ic_swapper* sw) {
   if (sw->live) return IC_OK;
-  if (hipStreamCreateWithFlags(&sw->s_out, hipStreamNonBlocking) != hipSuccess) return IC_EHIP;
-  if (hipStreamCreateWithFlags(&sw->s_in, hipStreamNonBlocking) != hipSuccess) return IC_EHIP;
-  if (hipEventCreateWithFlags(&sw->ev_start, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
+  if (!sw->s_out && hipStreamCreateWithFlags(&sw->s_out, hipStreamNonBlocking) != hipSuccess) return IC_EHIP;
+  if (!sw->s_in && hipStreamCreateWithFlags(&sw->s_in, hipStreamNonBlocking) != hipSuccess) return IC_EHIP;
+  if (!sw->ev_start && hipEventCreateWithFlags(&sw->ev_start, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
   for (Stage& s : sw->stages) {
-    if (hipEventCreateWithFlags(&s.free_, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
+    if (!s.free_ && hipEventCreateWithFlags(&s.free_, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
   }
   for (int d = 0; d < 2; ++d)
     for (hipEvent_t& e : sw->done[d])
-      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
+      if (!e && hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
   const size_t list_bytes = (sizeof(int32_t) * (size_t)sw->cfg.max_blocks + 15) / 16 * 16;
-  if (hipMalloc((void**)&sw->dev_ids, list_bytes * kIdSlots) != hipSuccess) return IC_EHIP;
+  if (!sw->dev_ids && hipMalloc((void**)&sw->dev_ids, list_bytes * kIdSlots) != hipSuccess) return IC_EHIP;
   for (IdSlot& s : sw->ids) {
-    if (hipHostMalloc((void**)&s.host, list_bytes, hipHostMallocDefault) != hipSuccess) return IC_EHIP;
-    if (hipEventCreateWithFlags(&s.ev, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
+    if (!s.host && hipHostMalloc((void**)&s.host, list_bytes, hipHostMallocDefault) != hipSuccess) return IC_EHIP;
+    if (!s.ev && hipEventCreateWithFlags(&s.ev, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
   }
   sw->live = true;
   return IC_OK;
