@@ -279,8 +279,22 @@ def ceilings_bench(args):
                 best = (tf, ghz)
         out[name] = {"TFLOPs": round(best[0], 1), "shader_GHz": round(best[1], 3),
                      "frac_vendor_peak": round(best[0] / MFMA_BF16_PEAK_TFLOPS, 4)}
+    # streaming read and plain copy of 1.25 GiB (the bytes one pack call moves), two buffer pairs alternating
+    n = 1280 << 20
+    bufs = [torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 256) for _ in range(4)]
+    hbm = {}
+    for name, mode in (("read", 0), ("copy", 1)):
+        best = 0.0
+        for rep in range(6):
+            src, dst = bufs[2 * (rep & 1)], bufs[2 * (rep & 1) + 1]
+            rc, g = B.hbm_ceiling(src.data_ptr(), dst.data_ptr(), n, mode, 5)
+            if rc != B.IC_OK:
+                raise RuntimeError(B.strerror(rc))
+            best = max(best, g)
+        hbm[name] = {"GBps": round(best, 1), "frac_vendor_peak": round(best / HBM_PEAK_GBPS, 4)}
     print(json.dumps({"metric": "MFMA-only loop rate, v_mfma_f32_32x32x16_bf16 on register operands", "unit": "TFLOP/s",
-                      "n_gpus": 1, "vendor_peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS, "operands": out}))
+                      "n_gpus": 1, "vendor_peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS, "operands": out,
+                      "hbm_vendor_peak_GBps": HBM_PEAK_GBPS, "hbm_streaming": hbm}))
 
 
 def saturation_bench(args):

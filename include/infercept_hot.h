@@ -403,6 +403,18 @@ int ic_prof_end(ic_pool* pool, ic_prof_stats* out);
 int ic_mfma_ceiling(const void* dev_operands, size_t operand_bytes, void* dev_sink, size_t sink_bytes,
                     int32_t iters, void* hip_stream, double* tflops, double* shader_ghz);
 
+/* Measurement aid: what a plain streaming kernel reaches on this GPU, for scale next to the 8 TB/s
+ * vendor figure.  mode 0 reads `bytes` of dev_src once per repetition (dev_dst: >= 16 bytes, may
+ * receive one 16-byte word); mode 1 copies dev_src to dev_dst (`bytes` each).  One-wave workgroups
+ * (1 KiB each for the copy, 8 KiB for the read), non-temporal loads and stores.  *gbps = bytes moved
+ * (read, or read + written) per second over `reps` back-to-back launches, by HIP events on
+ * hip_stream.  Synchronous.
+ *   bytes: a multiple of 8192, at most 2^31 KiB; reps 1 .. 10000; the two ranges must not overlap.
+ * Errors: IC_ENULL, IC_EINVAL, IC_EALIGN, IC_EHIP; nothing is launched on a validation error.
+ */
+int ic_hbm_ceiling(const void* dev_src, void* dev_dst, size_t bytes, int32_t mode, int32_t reps,
+                   void* hip_stream, double* gbps);
+
 #ifdef __cplusplus
 }
 #endif

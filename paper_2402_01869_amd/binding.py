@@ -33,7 +33,7 @@ EXPORTS = (
     "ic_tfwd_eval", "ic_waste_discard", "ic_waste_preserve", "ic_waste_swap", "ic_waste_chunked_discard",
     "ic_chunk_tokens", "ic_chunk_count", "ic_saturation_point", "ic_schedule_intercepted",
     "paged_attn_plan_create", "paged_attn_planned", "paged_attn_plan_destroy", "kv_write_span_planned",
-    "ic_mfma_ceiling", "ic_plan_image",
+    "ic_mfma_ceiling", "ic_plan_image", "ic_hbm_ceiling",
 )
 IC_CEILING_OPERAND_BYTES = 1 << 20
 IC_CEILING_SINK_BYTES = 256 * 512 * 4 + 256 * 16
@@ -547,3 +547,11 @@ def mfma_ceiling(dev_operands: int, operand_bytes: int, dev_sink: int, sink_byte
     rc = lib().ic_mfma_ceiling(C.c_void_p(dev_operands), C.c_size_t(operand_bytes), C.c_void_p(dev_sink),
                                C.c_size_t(sink_bytes), C.c_int32(iters), C.c_void_p(stream), C.byref(tf), C.byref(ghz))
     return rc, tf.value, ghz.value
+
+
+def hbm_ceiling(dev_src: int, dev_dst: int, nbytes: int, mode: int, reps: int, stream: int = 0):
+    """ic_hbm_ceiling: returns (rc, GB/s); mode 0 = streaming read, 1 = copy."""
+    g = C.c_double(0.0)
+    rc = lib().ic_hbm_ceiling(C.c_void_p(dev_src), C.c_void_p(dev_dst), C.c_size_t(nbytes), C.c_int32(mode),
+                              C.c_int32(reps), C.c_void_p(stream), C.byref(g))
+    return rc, g.value

@@ -105,3 +105,17 @@ def test_mfma_ceiling_reports_a_rate_and_a_clock():
             assert rc == B.IC_OK
         print(name, tf, ghz, flush=True)
         assert 50.0 < tf < 2600.0 and 0.3 < ghz < 2.6, (name, tf, ghz)
+
+
+@pytest.mark.gpu
+def test_hbm_ceiling_copy_is_exact_and_reports_a_rate():
+    """The copy mode of the measurement aid really copies (bit for bit) and both modes return a rate below the vendor
+    peak (plus timer slack)."""
+    n = 64 << 20
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device=DEV)
+    dst = torch.zeros(n, dtype=torch.uint8, device=DEV)
+    rc, g = B.hbm_ceiling(src.data_ptr(), dst.data_ptr(), n, 1, 3)
+    assert rc == B.IC_OK and 100.0 < g < 8800.0, g
+    assert torch.equal(src, dst)
+    rc, g = B.hbm_ceiling(src.data_ptr(), dst.data_ptr(), n, 0, 3)
+    assert rc == B.IC_OK and 100.0 < g < 8800.0, g

@@ -438,3 +438,14 @@ def test_launch_plan_covers_every_row_and_key_exactly_once(H, Hkv, D):
             pool.set_tuning(**tn)
             _check_plan_covers_every_row_once(pool, batch, desc)
         pool.close()
+
+
+def test_hbm_ceiling_rejects_bad_arguments_before_any_launch():
+    a, b = 0x100000, 0x900000   # never dereferenced: every call below fails validation first
+    assert B.hbm_ceiling(0, b, 1 << 20, 0, 1)[0] == B.IC_ENULL
+    assert B.hbm_ceiling(a, 0, 1 << 20, 1, 1)[0] == B.IC_ENULL
+    assert B.hbm_ceiling(a, b, 1024, 0, 1)[0] == B.IC_EINVAL          # not a multiple of 8 KiB
+    assert B.hbm_ceiling(a, b, 1 << 20, 2, 1)[0] == B.IC_EINVAL         # unknown mode
+    assert B.hbm_ceiling(a, b, 1 << 20, 1, 0)[0] == B.IC_EINVAL         # no repetitions
+    assert B.hbm_ceiling(a + 4, b, 1 << 20, 1, 1)[0] == B.IC_EALIGN
+    assert B.hbm_ceiling(a, a + (1 << 19), 1 << 20, 1, 1)[0] == B.IC_EINVAL   # overlapping copy
