@@ -189,3 +189,64 @@ def test_13b_shaped_layers_sampled():
     sw.close()
     for p in pools:
         p.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_sequences_of_swaps_in_both_directions(seed):
+    """Three to thirteen calls in random order and size, both directions in flight at once (on disjoint blocks, as
+    the caller must ensure), with and without syncs in between, one to five layers, two to four staging buffers:
+    every host buffer and every pool must end up as the per-layer memcpy oracle says."""
+    rng = np.random.default_rng(77000 + seed)
+    L, stages = int(rng.integers(1, 6)), int(rng.integers(2, 5))
+    H, D, nb = int(rng.choice([1, 2, 5])), int(rng.choice([64, 128])), int(rng.integers(8, 200))
+    max_blocks = int(rng.integers(1, nb + 1))
+    ly = Layers(L, nb, H, D, max_blocks, stages, seed)
+    model = [h.copy() for h in ly.host]          # what the pools must hold at the end
+    out_busy, in_busy = set(), set()             # blocks a queued swap still reads / writes
+    outs, keep = [], []
+
+    def drain():
+        ly.sw.sync()
+        out_busy.clear()
+        in_busy.clear()
+
+    for _ in range(int(rng.integers(3, 14))):
+        n = int(rng.integers(1, max_blocks + 1))
+        if rng.random() < 0.5:                   # swap-out: duplicates allowed, must not read what a swap-in writes
+            free = [b for b in range(nb) if b not in in_busy]
+            if not free:
+                drain()
+                free = list(range(nb))
+            ids = rng.choice(free, size=n).astype(np.int32)
+            stride = n * ly.bb + 16 * int(rng.integers(0, 3))
+            buf = B.PinnedBuffer(L * stride)
+            buf.array[:] = 0xEE
+            ly.sw.swap_out(ids, buf.ptr, stride)
+            out_busy |= set(ids.tolist())
+            outs.append((buf, stride, oracle.swap_out_layers(model, ids)))
+        else:                                    # swap-in: distinct blocks that no queued swap-out still reads
+            free = [b for b in range(nb) if b not in out_busy]
+            if len(free) < n:
+                drain()
+                free = list(range(nb))
+            ids = rng.permutation(free)[:n].astype(np.int32)
+            buf = B.PinnedBuffer(L * n * ly.bb)
+            buf.array[:] = rng.integers(0, 256, size=buf.nbytes, dtype=np.uint8)
+            ly.sw.swap_in(ids, buf.ptr, n * ly.bb)
+            oracle.swap_in_layers(model, ids, buf.array.reshape(L, n * ly.bb))
+            in_busy |= set(ids.tolist())
+            keep.append(buf)
+        if rng.random() < 0.3:
+            drain()
+    ly.sw.sync()
+    for buf, stride, want in outs:
+        n_bytes = want.shape[1]
+        for l in range(L):
+            assert np.array_equal(buf.array[l * stride: l * stride + n_bytes], want[l]), ("swap-out", l)
+    for l in range(L):
+        assert np.array_equal(ly.dev[l].cpu().numpy(), model[l]), ("pool", l)
+    ly.close()
+    for buf, _, _ in outs:
+        buf.close()
+    for buf in keep:
+        buf.close()
