@@ -281,6 +281,34 @@ def test_caller_stream_and_back_to_back_calls():
     pool.close()
 
 
+def test_two_pools_on_two_streams_share_the_side_stream():
+    """Two pools (two layers, say), each driven on a stream of its own with several calls in flight: their tile
+    kernels share the one side stream of the device, their row kernels the CUs; every call gives what it gives alone."""
+    H, D = 5, 128
+    rng = np.random.default_rng(808)
+    b1 = W.assemble_batch(H, D, 16, 512, [700, 33, 300, 1000, 2100], [200, 1, 300, 1, 1], rng)
+    b2 = W.assemble_batch(H, D, 16, 512, [515, 129, 64, 90, 1500], [130, 128, 1, 1, 1], rng)
+    bits1, q1 = W.make_host_inputs(b1, 4321, poison_unused=True)
+    bits2, q2 = W.make_host_inputs(b2, 4322, poison_unused=True)
+    want1, want2 = oracle.attn_batch(b1, bits1, q1), oracle.attn_batch(b2, bits2, q2)
+    pool1, keep1 = make_pool(bits1)
+    pool2, keep2 = make_pool(bits2)
+    r1, r2 = AttnRunner(pool1, b1, q1), AttnRunner(pool2, b2, q2)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for r, pool in ((r1, pool1), (r2, pool2)):
+        r.ws = torch.empty(pool.workspace_bytes(r.desc), dtype=torch.uint8, device=DEV)
+    torch.cuda.synchronize()
+    for _ in range(5):
+        pool1.paged_attn_mixed(r1.desc, r1.q.data_ptr(), r1.out.data_ptr(), r1.ws.data_ptr(), r1.ws.numel(), s1.cuda_stream)
+        pool2.paged_attn_mixed(r2.desc, r2.q.data_ptr(), r2.out.data_ptr(), r2.ws.data_ptr(), r2.ws.numel(), s2.cuda_stream)
+    s1.synchronize()
+    s2.synchronize()
+    assert max_abs_err(from_dev_bits(r1.out), want1) <= TOL
+    assert max_abs_err(from_dev_bits(r2.out), want2) <= TOL
+    pool1.close()
+    pool2.close()
+
+
 def test_gptj_decode_config_full():
     """64 decode sequences, contexts 512..2048, H16 D256: every output element against the oracle."""
     cfg = W.GPTJ_DECODE
