@@ -11,6 +11,8 @@ tfwd / waste_* / chunk_* / saturation_point / schedule_intercepted : the GPU-mem
     (Eq. 1-5), the saturation point and the interception schedule (Sections 3.2, 4.2, 4.3).
 swap_out_layers / swap_in_layers / swap_limit_tokens / swap_schedule : what the layer-by-layer,
     chunked swap of Section 4.1 leaves behind, its swap limit N_i and the split over iterations.
+attn_partial / merge_partials : the split-KV identity the GPU path relies on (not in the paper): a row's keys cut
+    into ranges, each giving (m, l, o~), merged by log-sum-exp; written out in numpy to pin the FORMULA.
 Every function is pinned by tests/test_oracle_pins.py; none is "parity unpinned".
 """
 from __future__ import annotations
@@ -142,6 +144,36 @@ def paged_attn(pool_bits, ctx_len, q_len, q_start, block_tables, q_bits, scale,
         block_tables.shape[1], _p(q_bits, C.c_uint16), float(scale), _p(out, C.c_double))
     _check(rc)
     return out
+
+
+def _bf16_to_f64(bits: np.ndarray) -> np.ndarray:
+    return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def attn_partial(pool_bits, table, q_row_bits, scale, k_begin: int, k_end: int, kv_head: int):
+    """Split-KV partial of ONE query row of one head over keys [k_begin, k_end) of a paged sequence:
+    m = max_t s_t, l = sum_t e^(s_t - m), o~ = sum_t e^(s_t - m) v_t, with s_t = scale * q . k_t (fp64).
+    pool_bits uint16 [blocks][2][Hkv][B][D]; table = the sequence's block ids; q_row_bits uint16 [D]."""
+    B = pool_bits.shape[3]
+    q = _bf16_to_f64(q_row_bits)
+    s, v = [], []
+    for t in range(int(k_begin), int(k_end)):
+        blk, slot = int(table[t // B]), t % B
+        s.append(float(scale) * float(np.dot(q, _bf16_to_f64(pool_bits[blk, 0, kv_head, slot]))))
+        v.append(_bf16_to_f64(pool_bits[blk, 1, kv_head, slot]))
+    s = np.array(s)
+    m = float(s.max())
+    w = np.exp(s - m)
+    return m, float(w.sum()), (w[:, None] * np.array(v)).sum(axis=0)
+
+
+def merge_partials(parts):
+    """Merge of split-KV partials [(m_p, l_p, o~_p), ...]: m = max_p m_p, l = sum_p l_p e^(m_p - m),
+    o = sum_p o~_p e^(m_p - m) / l."""
+    m = max(p[0] for p in parts)
+    l = sum(p[1] * np.exp(p[0] - m) for p in parts)
+    o = sum(p[2] * np.exp(p[0] - m) for p in parts)
+    return o / l
 
 
 def attn_batch(batch, pool_bits, q_bits) -> np.ndarray:

@@ -637,3 +637,28 @@ def test_stored_oracle_values_have_not_moved():
     spec.loader.exec_module(mod)
     for name, fn in mod.FILES.items():
         assert open(os.path.join(here, name)).read() == fn(), name
+
+
+def test_split_kv_merge_reproduces_the_unsplit_row():
+    """The identity the GPU path's split-KV rests on (it is not in the paper): cut a row's keys into ranges, take
+    (m, l, o~) of each, merge by log-sum-exp, and the unsplit attention row comes back to 1e-13.  Partitions of one
+    key, of uneven sizes, in any order; a grouped pool (query head 5 reads K/V head 1)."""
+    rng = np.random.default_rng(2024)
+    H, Hkv, D, ctx = 6, 2, 64, 333
+    pool_bits = W.randn_bf16((32, 2, Hkv, 16, D), rng)
+    table = rng.permutation(32)[: (ctx + 15) // 16].astype(np.int32)
+    q_bits = W.randn_bf16((1, H, D), rng)
+    scale = 1.0 / np.sqrt(D)
+    want = oracle.paged_attn(pool_bits, [ctx], [1], [0], table[None, :], q_bits, scale)   # [1][H][D], the C oracle
+    for head in (0, 5):
+        kvh = head // (H // Hkv)
+        whole = oracle.attn_partial(pool_bits, table, q_bits[0, head], scale, 0, ctx, kvh)
+        assert np.allclose(whole[2] / whole[1], want[0, head], rtol=0, atol=1e-13)
+        for cuts in ([0, 64, 128, 333], [0, 1, 2, 330, 333], [0, 200, 333], sorted({0, ctx} | set(rng.integers(1, ctx, 9).tolist()))):
+            parts = [oracle.attn_partial(pool_bits, table, q_bits[0, head], scale, a, b, kvh) for a, b in zip(cuts, cuts[1:])]
+            for order in (parts, parts[::-1]):
+                assert np.allclose(oracle.merge_partials(order), want[0, head], rtol=0, atol=1e-13)
+    # a wrong merge (forgetting the e^(m_p - m) factors) is caught
+    parts = [oracle.attn_partial(pool_bits, table, q_bits[0, 0], scale, a, b, 0) for a, b in ((0, 100), (100, 333))]
+    wrong = sum(p[2] for p in parts) / sum(p[1] for p in parts)
+    assert np.abs(wrong - want[0, 0]).max() > 1e-3
