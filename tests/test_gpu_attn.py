@@ -388,6 +388,42 @@ def test_mixed_13b_config_sampled():
     pool.close()
 
 
+def test_gqa_70b_config_sampled():
+    """70B-shaped grouped-query batch (64 query heads over 8 K/V heads) at full size, in the launch configuration the
+    benchmark times (group kernel for the decode rows, head-group tiles for the chunks): every decode row and a
+    deterministic sample of span rows, all 64 heads of each."""
+    cfg = W.GQA_70B
+    batch = W.make_batch(cfg)
+    Hkv = cfg.num_kv_heads
+    pool_t = torch.empty(W.pool_shape(cfg.pool_blocks, Hkv, 16, cfg.head_dim), dtype=torch.bfloat16, device=DEV)
+    W.fill_pool_device_normal(pool_t, cfg.seed)
+    q_bits = W.randn_bf16((batch.total_q_rows, cfg.num_heads, cfg.head_dim), np.random.default_rng(cfg.seed))
+    pool = B.KvPool.from_tensor(pool_t, cfg.num_heads, cfg.head_dim, num_kv_heads=Hkv)
+    r = AttnRunner(pool, batch, q_bits, flags=B.IC_FLAG_TRUSTED)
+    out = r.run()
+    assert np.isfinite(W.bf16_bits_to_f64(out)).all()
+
+    def fetch(ids):
+        return from_dev_bits(pool_t.view(torch.int16)[torch.from_numpy(ids).to(DEV)])
+
+    span_rows = [0, 1, 3, 4, 15, 16, 17, 31, 32, 33, 127, 128, 255, 256, 300, 511]   # 4-row head-group tile edges too
+    rec = Recorded()
+    for s0 in range(0, batch.num_seqs, 8):
+        seqs = list(range(s0, min(batch.num_seqs, s0 + 8)))
+        small, sub = W.compact_referenced(batch, seqs, fetch)
+        iseq, irow = [], []
+        for j, s in enumerate(seqs):
+            rows = [0] if batch.q_len[s] == 1 else span_rows
+            iseq += [j] * len(rows); irow += rows
+        want = oracle.paged_attn_items(small, sub.ctx_len, sub.q_len, sub.q_start, sub.block_tables, q_bits,
+                                       sub.scale, iseq, irow)
+        grow = [int(sub.q_start[j]) + i for j, i in zip(iseq, irow)]
+        rec.add(W.bf16_bits_to_f64(out[grow]), want)
+    rec.report("gqa_70b")
+    assert rec.worst <= TOL, rec.worst
+    pool.close()
+
+
 @pytest.mark.timeout(900)
 def test_long_context_config_sampled():
     """Long-context stress at full size (128 GiB pool, 16 spans of 2048 rows on 16384-token prefixes): every
