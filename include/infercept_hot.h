@@ -114,8 +114,9 @@ typedef struct {
 size_t paged_attn_mixed_workspace_bytes(const ic_pool* pool, const ic_batch_desc* desc);
 
 /*
- * dev_q, dev_out: device bf16 [total_q_rows][num_heads][head_dim].  dev_workspace: device, at
- * least paged_attn_mixed_workspace_bytes() (IC_ESIZE otherwise); its contents are scratch.
+ * dev_q, dev_out: device bf16 [total_q_rows][num_heads][head_dim].  dev_workspace: device, 256-byte
+ * aligned (IC_EALIGN otherwise; device allocators return such addresses), at least
+ * paged_attn_mixed_workspace_bytes() (IC_ESIZE otherwise); its contents are scratch.
  * Deterministic: the same inputs give the same bits on every call.
  */
 int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q, void* dev_out,
@@ -144,7 +145,8 @@ int kv_write_span(ic_pool* pool, const ic_batch_desc* desc, const void* dev_k_ne
  * and tuning (IC_EINVAL otherwise) with nothing but kernel launches.  The workspace belongs to the
  * plan until paged_attn_plan_destroy; its partial-result area is reused by every run, so runs of one
  * plan must be ordered on one stream (after the stream the plan was created on has passed the
- * upload).  Results are those of paged_attn_mixed, bit for bit.
+ * upload).  dev_workspace as for paged_attn_mixed (256-byte aligned, at least its workspace bytes).
+ * Results are those of paged_attn_mixed, bit for bit.
  */
 typedef struct ic_plan ic_plan;
 int paged_attn_plan_create(ic_pool* pool, const ic_batch_desc* desc, void* dev_workspace, size_t workspace_bytes,
