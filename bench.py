@@ -292,9 +292,30 @@ def ceilings_bench(args):
                 raise RuntimeError(B.strerror(rc))
             best = max(best, g)
         hbm[name] = {"GBps": round(best, 1), "frac_vendor_peak": round(best / HBM_PEAK_GBPS, 4)}
+    del bufs
+    # the decode kernels' access pattern without their arithmetic: the blocks of the 13B-shaped batch's decode
+    # sequences (randomly placed) and as many consecutive blocks, tile by tile
+    acfg = W.MIXED_13B
+    batch = W.make_batch(acfg)
+    pool_t = torch.empty(W.pool_shape(acfg.pool_blocks, acfg.num_heads, 16, acfg.head_dim), dtype=torch.bfloat16, device=dev)
+    W.fill_pool_device_normal(pool_t, acfg.seed)
+    pool = B.KvPool.from_tensor(pool_t, acfg.num_heads, acfg.head_dim)
+    ids = np.concatenate([batch.blocks_of(s) for s in range(batch.num_seqs) if batch.q_len[s] == 1]).astype(np.int32)
+    sink16 = torch.zeros(16, dtype=torch.uint8, device=dev)
+    paged = {}
+    for name, lists in (("random_blocks", [ids, ids[::-1].copy()]),
+                        ("consecutive_blocks", [np.arange(len(ids), dtype=np.int32),
+                                                np.arange(len(ids), 2 * len(ids), dtype=np.int32)])):
+        best = 0.0
+        for rep in range(6):   # two lists alternate so that no pass finds its blocks in the last-level cache
+            best = max(best, pool.paged_read_ceiling(lists[rep & 1], sink16.data_ptr(), 1))
+        paged[name] = {"GBps": round(best, 1), "frac_vendor_peak": round(best / HBM_PEAK_GBPS, 4),
+                       "bytes": float(len(ids)) * pool.block_bytes}
+    pool.close()
     print(json.dumps({"metric": "MFMA-only loop rate, v_mfma_f32_32x32x16_bf16 on register operands", "unit": "TFLOP/s",
                       "n_gpus": 1, "vendor_peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS, "operands": out,
-                      "hbm_vendor_peak_GBps": HBM_PEAK_GBPS, "hbm_streaming": hbm}))
+                      "hbm_vendor_peak_GBps": HBM_PEAK_GBPS, "hbm_streaming": hbm,
+                      "paged_tile_read_13b_decode_blocks": paged}))
 
 
 def saturation_bench(args):

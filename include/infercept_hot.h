@@ -417,6 +417,16 @@ int ic_mfma_ceiling(const void* dev_operands, size_t operand_bytes, void* dev_si
 int ic_hbm_ceiling(const void* dev_src, void* dev_dst, size_t bytes, int32_t mode, int32_t reps,
                    void* hip_stream, double* gbps);
 
+/* Measurement aid: the streaming-read rate of the decode kernels' ACCESS PATTERN with the arithmetic
+ * taken out.  One one-wave workgroup per (listed block, K/V head) loads that head's K tile and V tile
+ * of the block (block_size x head_dim bf16 each, non-temporal 16-byte loads) and folds them into a
+ * word.  *gbps = n * kv_block_bytes * reps bytes over the time of `reps` back-to-back launches.
+ * host_ids: n block ids in [0, num_blocks), duplicates allowed; dev_sink: device, 16 bytes, may be
+ * written.  Allocates and frees its own device copy of the id list.  Synchronous.
+ * Errors: IC_ENULL, IC_EINVAL, IC_ERANGE, IC_EALIGN, IC_EHIP. */
+int ic_paged_read_ceiling(const ic_pool* pool, const int32_t* host_ids, int32_t n, void* dev_sink,
+                          int32_t reps, void* hip_stream, double* gbps);
+
 #ifdef __cplusplus
 }
 #endif

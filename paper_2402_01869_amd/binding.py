@@ -33,7 +33,7 @@ EXPORTS = (
     "ic_tfwd_eval", "ic_waste_discard", "ic_waste_preserve", "ic_waste_swap", "ic_waste_chunked_discard",
     "ic_chunk_tokens", "ic_chunk_count", "ic_saturation_point", "ic_schedule_intercepted",
     "paged_attn_plan_create", "paged_attn_planned", "paged_attn_plan_destroy", "kv_write_span_planned",
-    "ic_mfma_ceiling", "ic_plan_image", "ic_hbm_ceiling",
+    "ic_mfma_ceiling", "ic_plan_image", "ic_hbm_ceiling", "ic_paged_read_ceiling",
 )
 IC_CEILING_OPERAND_BYTES = 1 << 20
 IC_CEILING_SINK_BYTES = 256 * 512 * 4 + 256 * 16
@@ -292,6 +292,16 @@ class KvPool:
         out["row_dst"] = sec(out["off_row_dst"], int(desc.struct.total_q_rows))
         out["partial_slots"] = info["partial_slots"]
         return out
+
+    def paged_read_ceiling(self, ids, dev_sink: int, reps: int = 1, stream: int = 0, check: bool = True):
+        """ic_paged_read_ceiling: GB/s of a compute-free read of the listed blocks, tile by tile (rc, GB/s if not check)."""
+        ids = _i32(ids)
+        g = C.c_double(0.0)
+        rc = lib().ic_paged_read_ceiling(self._h, _ptr(ids), int(ids.shape[0]), C.c_void_p(dev_sink), C.c_int32(reps),
+                                         C.c_void_p(stream), C.byref(g))
+        if check and rc != IC_OK:
+            raise InferceptError(rc, "ic_paged_read_ceiling")
+        return g.value if check else (int(rc), g.value)
 
     def workspace_bytes(self, desc: HostDesc) -> int:
         return int(lib().paged_attn_mixed_workspace_bytes(self._h, C.byref(desc.struct)))

@@ -65,8 +65,67 @@ __global__ __launch_bounds__(64) void hbm_read_kernel(const u32x4* __restrict__ 
   if ((x[0] ^ x[1] ^ x[2] ^ x[3]) == 0x9e3779b9u) dst[0] = x;  // keeps the loads alive; true about once in 2^32
 }
 
+// The decode kernels' access pattern with the arithmetic taken out: one one-wave workgroup per (listed block, K/V
+// head) loads that head's K tile and V tile (block_size x head_dim bf16 each) and folds them into one word.
+template <int LOADS>  // 16-byte loads per lane and tile: tile bytes / 1024
+__global__ __launch_bounds__(64) void paged_read_kernel(const char* __restrict__ pool, const int32_t* __restrict__ ids,
+                                                        int Hk, size_t tile_bytes, u32x4* __restrict__ sink) {
+  const int b = blockIdx.x / Hk, h = blockIdx.x - b * Hk;
+  const char* k = pool + (size_t)ids[b] * (2 * (size_t)Hk * tile_bytes) + (size_t)h * tile_bytes + threadIdx.x * 16;
+  const char* v = k + (size_t)Hk * tile_bytes;
+  u32x4 x = {0u, 0u, 0u, 0u};
+  u32x4 a[LOADS], c[LOADS];
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) a[i] = __builtin_nontemporal_load((const u32x4*)(k + i * 1024));
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) c[i] = __builtin_nontemporal_load((const u32x4*)(v + i * 1024));
+#pragma unroll
+  for (int i = 0; i < LOADS; ++i) x ^= a[i] ^ c[i];
+  if ((x[0] ^ x[1] ^ x[2] ^ x[3]) == 0x9e3779b9u) sink[0] = x;  // keeps the loads alive
+}
+
 }  // namespace
 }  // namespace ic
+
+extern "C" int ic_paged_read_ceiling(const ic_pool* pool, const int32_t* host_ids, int32_t n, void* dev_sink,
+                                     int32_t reps, void* hip_stream, double* gbps) {
+  using namespace ic;
+  if (!pool || !host_ids || !dev_sink || !gbps) return IC_ENULL;
+  const PoolView pv = pool_view(pool);
+  if (n < 1 || reps < 1 || reps > 10000 || (uint64_t)n * (uint64_t)pv.cfg.num_kv_heads > 0x7fffffffull) return IC_EINVAL;
+  const int rc0 = ic_check_ids(&pv.cfg, host_ids, n, 0);
+  if (rc0 != IC_OK) return rc0;
+  if ((uintptr_t)dev_sink & 15) return IC_EALIGN;
+  hipStream_t st = (hipStream_t)hip_stream;
+  int32_t* dev_ids = nullptr;
+  if (hipMalloc((void**)&dev_ids, sizeof(int32_t) * (size_t)n) != hipSuccess) return IC_EHIP;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = IC_OK;
+  float ms = 0.f;
+  if (hipMemcpy(dev_ids, host_ids, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice) != hipSuccess ||
+      hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess || hipEventRecord(e0, st) != hipSuccess)
+    rc = IC_EHIP;
+  const int Hk = pv.cfg.num_kv_heads;
+  const size_t tile_bytes = (size_t)pv.cfg.block_size * pv.cfg.head_dim * 2;
+  const dim3 grid((uint32_t)n * (uint32_t)Hk), block(64);
+  for (int r = 0; rc == IC_OK && r < reps; ++r) {
+    switch (pv.cfg.head_dim) {
+      case 64: hipLaunchKernelGGL(paged_read_kernel<2>, grid, block, 0, st, pv.base, dev_ids, Hk, tile_bytes, (u32x4*)dev_sink); break;
+      case 128: hipLaunchKernelGGL(paged_read_kernel<4>, grid, block, 0, st, pv.base, dev_ids, Hk, tile_bytes, (u32x4*)dev_sink); break;
+      default: hipLaunchKernelGGL(paged_read_kernel<8>, grid, block, 0, st, pv.base, dev_ids, Hk, tile_bytes, (u32x4*)dev_sink); break;
+    }
+    if (hipGetLastError() != hipSuccess) rc = IC_EHIP;
+  }
+  if (rc == IC_OK && (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                      hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+    rc = IC_EHIP;
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(dev_ids);
+  if (rc != IC_OK) return rc;
+  *gbps = ms > 0.f ? (double)n * (double)pv.block_bytes * reps / ((double)ms * 1e-3) / 1e9 : 0.0;
+  return IC_OK;
+}
 
 extern "C" int ic_hbm_ceiling(const void* dev_src, void* dev_dst, size_t bytes, int32_t mode, int32_t reps,
                               void* hip_stream, double* gbps) {

@@ -119,3 +119,19 @@ def test_hbm_ceiling_copy_is_exact_and_reports_a_rate():
     assert torch.equal(src, dst)
     rc, g = B.hbm_ceiling(src.data_ptr(), dst.data_ptr(), n, 0, 3)
     assert rc == B.IC_OK and 100.0 < g < 8800.0, g
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("D", [64, 128, 256])
+def test_paged_read_ceiling_runs_on_every_head_dim(D):
+    """The compute-free read of listed blocks (duplicates allowed) returns a plausible rate and leaves the pool alone."""
+    H, nb = 3, 300
+    pool_t = torch.randint(-30000, 30000, (nb, 2, H, 16, D), dtype=torch.int16, device=DEV)
+    before = pool_t.clone()
+    pool = B.KvPool.from_tensor(pool_t, H, D)
+    sink = torch.zeros(16, dtype=torch.uint8, device=DEV)
+    ids = np.random.default_rng(D).integers(0, nb, size=1000).astype(np.int32)
+    g = pool.paged_read_ceiling(ids, sink.data_ptr(), 3)
+    assert 1.0 < g < 8800.0, g
+    assert torch.equal(pool_t, before)
+    pool.close()

@@ -449,3 +449,12 @@ def test_hbm_ceiling_rejects_bad_arguments_before_any_launch():
     assert B.hbm_ceiling(a, b, 1 << 20, 1, 0)[0] == B.IC_EINVAL         # no repetitions
     assert B.hbm_ceiling(a + 4, b, 1 << 20, 1, 1)[0] == B.IC_EALIGN
     assert B.hbm_ceiling(a, a + (1 << 19), 1 << 20, 1, 1)[0] == B.IC_EINVAL   # overlapping copy
+
+
+def test_paged_read_ceiling_rejects_bad_arguments_before_any_launch():
+    pool = B.KvPool(B.make_cfg(64, 4, 64), 0x10000, 64 * 16 * 2 * 4 * 64 * 2)   # base never dereferenced
+    assert pool.paged_read_ceiling([0, 1], 0, 1, check=False)[0] == B.IC_ENULL
+    assert pool.paged_read_ceiling([0, 64], 0x2000, 1, check=False)[0] == B.IC_ERANGE
+    assert pool.paged_read_ceiling([0, 1], 0x2000, 0, check=False)[0] == B.IC_EINVAL
+    assert pool.paged_read_ceiling([0, 1], 0x2008, 1, check=False)[0] == B.IC_EALIGN
+    pool.close()
