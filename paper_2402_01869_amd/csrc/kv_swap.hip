@@ -25,10 +25,21 @@ __global__ __launch_bounds__(kThreads) void swap_blocks_kernel(char* __restrict_
                                                                char* __restrict__ staging,
                                                                const int32_t* __restrict__ ids,
                                                                uint32_t block_bytes,
-                                                               uint32_t chunks_per_block) {
+                                                               uint32_t chunks_per_block, uint32_t n_blocks) {
+  // Workgroups are dealt to the 8 XCDs round-robin by index.  Within every full group of 8 listed blocks, XCD x
+  // (index = x mod 8) takes block 8 g + x whole, so that one block's bytes go through one XCD's L2 and address
+  // translation; the last n % 8 blocks are dealt chunk by chunk.
   const uint32_t wg = blockIdx.x;
-  const uint32_t i = wg / chunks_per_block;
-  const uint32_t c = wg - i * chunks_per_block;
+  const uint32_t group_wgs = 8u * chunks_per_block;
+  const uint32_t g = wg / group_wgs, r = wg - g * group_wgs;
+  uint32_t i, c;
+  if ((g + 1u) * 8u <= n_blocks) {
+    i = g * 8u + (r & 7u);
+    c = r >> 3;
+  } else {
+    i = g * 8u + r / chunks_per_block;
+    c = r % chunks_per_block;
+  }
   const int64_t id = ids[i];
   const char* src;
   char* dst;
@@ -61,7 +72,7 @@ hipError_t launch_swap(char* pool, char* staging, const int32_t* dev_ids, int32_
   const uint64_t grid = (uint64_t)n * chunks;
   if (grid > 0x7fffffffull || block_bytes > 0xffffffffull) return hipErrorInvalidValue;
   hipLaunchKernelGGL(swap_blocks_kernel<PACK>, dim3((uint32_t)grid), dim3(kThreads), 0, st, pool,
-                     staging, dev_ids, (uint32_t)block_bytes, chunks);
+                     staging, dev_ids, (uint32_t)block_bytes, chunks, (uint32_t)n);
   return hipGetLastError();
 }
 
