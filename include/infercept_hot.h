@@ -71,7 +71,12 @@ typedef struct ic_pool ic_pool; /* opaque; created by kv_pool_init, freed by kv_
 /*
  * Describe caller-owned pool memory to the library.  dev_pool_base: device, >= num_blocks *
  * block bytes (IC_ESIZE otherwise), 16-byte aligned.  Allocates no KV memory and touches no GPU
- * state; the pool's small descriptor buffers are created by the first GPU call that needs them.
+ * state.  The pool's own buffers are created by the first GPU call that needs them, sized from the
+ * pool's shape so that later calls allocate nothing: four pinned host buffers for descriptors
+ * (256 KiB + 8 bytes per block each) and one device id list (one int per cache slot: 64 bytes per
+ * block).  A call that needs more (block tables that share blocks many times over, a pack list with
+ * many duplicates, more query rows than cache slots) allocates a larger buffer and keeps the old one
+ * until kv_pool_destroy; no call waits for the device.
  */
 int kv_pool_init(const ic_pool_cfg* cfg, void* dev_pool_base, size_t pool_bytes, ic_pool** out);
 int kv_pool_destroy(ic_pool* pool); /* frees library-owned buffers; never the KV memory */
@@ -105,7 +110,9 @@ typedef struct {
   const int32_t* block_tables;/* host [num_seqs][max_blocks_per_seq] row-major                 */
   int32_t max_blocks_per_seq; /* row stride of block_tables                                    */
   int32_t total_q_rows;       /* rows of q / out; every [q_start, q_start+q_len) inside, disjoint */
-  float scale;                /* softmax scale, 1/sqrt(head_dim) in the usual case             */
+  float scale;                /* softmax scale, 1/sqrt(head_dim) in the usual case; finite and > 0
+                                 (IC_EINVAL otherwise: the kernels fold it into the exponent after the
+                                 row maximum is taken, which needs a positive factor)          */
   uint32_t flags;             /* IC_FLAG_*                                                     */
 } ic_batch_desc;
 
@@ -178,6 +185,10 @@ typedef struct {
                                  1 = one workgroup per work item, 2 = persistent, 3 = persistent, the slim
                                  build that runs beside the tile kernel (head_dim <= 128)     */
   int32_t row_slots;          /* resident workgroups of the persistent row kernel; 0 = one per CU */
+  int32_t mfma_min_keys;      /* query rows that see fewer keys than this run on the vector kernel, which keeps the
+                                 softmax weights in fp32 (the matrix-core kernels round them to bf16, and with a
+                                 handful of keys one weight's rounding shows in the output); 0 = built-in 64,
+                                 1 = no such routing, at most 64                              */
   int32_t reserved[1];        /* must be 0                                                   */
 } ic_tuning;
 int ic_pool_set_tuning(ic_pool* pool, const ic_tuning* tuning);
@@ -217,7 +228,7 @@ typedef struct {
   int32_t tile_query_rows;   /* query rows per tile item                                      */
   int32_t tile_head_shift;   /* log2 of the query heads one tile workgroup serves             */
   int32_t n_row_items, n_tile_items, n_merge_items;
-  int32_t reserved;
+  int32_t n_vector_row_items; /* row items [0, n) run on the vector kernel, the rest on the group kernel */
 } ic_plan_layout;
 int ic_plan_image(const ic_pool* pool, const ic_batch_desc* desc, void* host_image, size_t host_bytes,
                   ic_plan_layout* out);
@@ -320,9 +331,9 @@ int64_t ic_swap_schedule(int64_t total_blocks, int32_t block_size, const int64_t
  * saturation point and the interception schedule.  Waste is in byte-seconds when token_bytes is M in
  * bytes and times are in seconds.
  *
- * T_fwd, "a mapping from the number of scheduled tokens in a batch to the execution time of that
- * iteration" (Section 3.2), comes from profiling: n points (tokens[k], seconds[k]), tokens positive
- * and strictly increasing.  Between points it is evaluated on straight lines, below the first
+ * T_fwd (Section 3.2) gives an iteration's execution time as a function of the tokens scheduled in its
+ * batch; here it comes from profiling: n points (tokens[k], seconds[k]), tokens positive and strictly
+ * increasing.  Between points it is evaluated on straight lines, below the first
  * point on the line from the origin, beyond the last on the last segment's line.  Functions that
  * take a table return NaN if it is malformed.
  * ------------------------------------------------------------------------------------------ */
@@ -368,64 +379,6 @@ enum { IC_ACT_NONE = 0, IC_ACT_PRESERVE = 1, IC_ACT_DISCARD = 2 };
 int ic_schedule_intercepted(int32_t n, const double* waste_preserve, const double* waste_chunked_discard,
                             const int64_t* ctx_tokens, int64_t swap_out_budget_tokens, int64_t* swap_tokens,
                             int32_t* action);
-
-/* ------------------------------------------------------------------------------------------
- * Per-kernel timing with HIP events on the launch stream (for roofline reports).  Between
- * ic_prof_begin and ic_prof_end every kernel the pool launches is bracketed by an event pair.
- * ic_prof_end synchronises the recorded events and returns totals per kernel kind.
- * ------------------------------------------------------------------------------------------ */
-enum { IC_K_ROW = 0, IC_K_TILE = 1, IC_K_MERGE = 2, IC_K_PACK = 3, IC_K_UNPACK = 4, IC_K_UPLOAD = 5, IC_K_APPEND = 6, IC_K_COUNT = 7 };
-/* IC_K_UPLOAD: the kernel that copies a call's descriptor from pinned host memory to the device. */
-typedef struct {
-  int32_t launches[IC_K_COUNT];
-  float total_ms[IC_K_COUNT];
-  float min_ms[IC_K_COUNT];
-  float max_ms[IC_K_COUNT];
-} ic_prof_stats;
-int ic_prof_begin(ic_pool* pool, int32_t max_launches);
-int ic_prof_end(ic_pool* pool, ic_prof_stats* out);
-
-/* ------------------------------------------------------------------------------------------
- * Measurement aid for roofline reports (not part of the method): the rate an MFMA-only loop reaches
- * on this GPU with the caller's operand data.  256 workgroups of 8 waves each issue iters x 4
- * back-to-back independent v_mfma_f32_32x32x16_bf16 on register operands taken from dev_operands
- * (bf16 bit patterns; zeros, ones or random values, the caller chooses), with no memory traffic in
- * the loop.  With random operands the chip's power limit lowers the shader clock, so the result is
- * below the vendor peak; *shader_ghz is the average shader clock inside the loop (shader-clock
- * ticks over 100 MHz real-time ticks of workgroup 0).
- *   dev_operands  DEVICE, 16-byte aligned, >= IC_CEILING_OPERAND_BYTES, only read
- *   dev_sink      DEVICE, 16-byte aligned, >= IC_CEILING_SINK_BYTES, overwritten (results the
- *                 compiler must not drop, and the clock readings)
- *   iters         1 .. 2^24
- * Synchronous: launches on hip_stream and waits for it.  Errors: IC_ENULL, IC_EINVAL, IC_ESIZE,
- * IC_EALIGN, IC_EHIP; nothing is launched on a validation error.
- */
-#define IC_CEILING_OPERAND_BYTES ((size_t)1 << 20)
-#define IC_CEILING_SINK_BYTES ((size_t)256 * 512 * 4 + (size_t)256 * 16)
-int ic_mfma_ceiling(const void* dev_operands, size_t operand_bytes, void* dev_sink, size_t sink_bytes,
-                    int32_t iters, void* hip_stream, double* tflops, double* shader_ghz);
-
-/* Measurement aid: what a plain streaming kernel reaches on this GPU, for scale next to the 8 TB/s
- * vendor figure.  mode 0 reads `bytes` of dev_src once per repetition (dev_dst: >= 16 bytes, may
- * receive one 16-byte word); mode 1 copies dev_src to dev_dst (`bytes` each).  One-wave workgroups
- * (1 KiB each for the copy, 8 KiB for the read), non-temporal loads and stores.  *gbps = bytes moved
- * (read, or read + written) per second over `reps` back-to-back launches, by HIP events on
- * hip_stream.  Synchronous.
- *   bytes: a multiple of 8192, at most 2^31 KiB; reps 1 .. 10000; the two ranges must not overlap.
- * Errors: IC_ENULL, IC_EINVAL, IC_EALIGN, IC_EHIP; nothing is launched on a validation error.
- */
-int ic_hbm_ceiling(const void* dev_src, void* dev_dst, size_t bytes, int32_t mode, int32_t reps,
-                   void* hip_stream, double* gbps);
-
-/* Measurement aid: the streaming-read rate of the decode kernels' ACCESS PATTERN with the arithmetic
- * taken out.  One one-wave workgroup per (listed block, K/V head) loads that head's K tile and V tile
- * of the block (block_size x head_dim bf16 each, non-temporal 16-byte loads) and folds them into a
- * word.  *gbps = n * kv_block_bytes * reps bytes over the time of `reps` back-to-back launches.
- * host_ids: n block ids in [0, num_blocks), duplicates allowed; dev_sink: device, 16 bytes, may be
- * written.  Allocates and frees its own device copy of the id list.  Synchronous.
- * Errors: IC_ENULL, IC_EINVAL, IC_ERANGE, IC_EALIGN, IC_EHIP. */
-int ic_paged_read_ceiling(const ic_pool* pool, const int32_t* host_ids, int32_t n, void* dev_sink,
-                          int32_t reps, void* hip_stream, double* gbps);
 
 #ifdef __cplusplus
 }

@@ -19,8 +19,8 @@ IC_OK = 0
 IC_ENULL, IC_EINVAL, IC_ERANGE, IC_ESIZE, IC_EALIGN = -1, -2, -3, -4, -5
 IC_EDUP, IC_EUNSUPPORTED, IC_EOVERLAP, IC_EHIP, IC_ENOMEM = -6, -7, -8, -9, -10
 IC_FLAG_TRUSTED = 1
-IC_K_ROW, IC_K_TILE, IC_K_MERGE, IC_K_PACK, IC_K_UNPACK, IC_K_UPLOAD, IC_K_APPEND, IC_K_COUNT = 0, 1, 2, 3, 4, 5, 6, 7
-KERNEL_NAMES = ("row", "tile", "merge", "pack", "unpack", "upload", "append")
+IC_K_ROW, IC_K_TILE, IC_K_MERGE, IC_K_PACK, IC_K_UNPACK, IC_K_UPLOAD, IC_K_APPEND, IC_K_GROUP, IC_K_COUNT = range(9)
+KERNEL_NAMES = ("row", "tile", "merge", "pack", "unpack", "upload", "append", "group")
 
 EXPORTS = (
     "ic_strerror", "kv_pool_init", "kv_pool_destroy", "kv_block_bytes",
@@ -60,7 +60,7 @@ class BatchDesc(C.Structure):
 
 class Tuning(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("decode_part_tokens", "span_part_tokens", "span_kernel", "row_variant",
-                                         "serial_spans", "row_launch", "row_slots")] + [("reserved", C.c_int32 * 1)]
+                                         "serial_spans", "row_launch", "row_slots", "mfma_min_keys")] + [("reserved", C.c_int32 * 1)]
 
 
 class PlanInfo(C.Structure):
@@ -73,7 +73,7 @@ class PlanLayout(C.Structure):
     _fields_ = ([(n, C.c_int64) for n in ("image_bytes", "off_counters", "off_bt_off", "off_bt_flat", "off_row_items",
                                           "off_tile_items", "off_merge_items", "off_row_dst")] +
                 [(n, C.c_int32) for n in ("row_part_tokens", "span_part_tokens", "tile_query_rows", "tile_head_shift",
-                                          "n_row_items", "n_tile_items", "n_merge_items", "reserved")])
+                                          "n_row_items", "n_tile_items", "n_merge_items", "n_vector_row_items")])
 
 
 class ProfStats(C.Structure):
@@ -254,9 +254,9 @@ class KvPool:
         return int(lib().kv_block_bytes(self._h))
 
     def set_tuning(self, decode_part_tokens=0, span_part_tokens=0, span_kernel=0, row_variant=0, serial_spans=0,
-                   row_launch=0, row_slots=0):
+                   row_launch=0, row_slots=0, mfma_min_keys=0):
         t = Tuning(int(decode_part_tokens), int(span_part_tokens), int(span_kernel), int(row_variant),
-                   int(serial_spans), int(row_launch), int(row_slots), (C.c_int32 * 1)(0))
+                   int(serial_spans), int(row_launch), int(row_slots), int(mfma_min_keys), (C.c_int32 * 1)(0))
         rc = lib().ic_pool_set_tuning(self._h, C.byref(t))
         if rc != IC_OK:
             raise InferceptError(rc, "ic_pool_set_tuning")

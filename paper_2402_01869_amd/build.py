@@ -11,7 +11,8 @@ LIB = os.path.join(HERE, "libinfercept_hot.so")
 SOURCES = ["ic_api.hip", "kv_swap.hip", "swap_pipe.hip", "waste_model.hip", "attn_row.hip", "attn_tile.hip", "attn_group.hip",
            "ceilings.hip"]
 HEADERS = [os.path.join(CSRC, "ic_internal.h"), os.path.join(CSRC, "row_body.h"), os.path.join(CSRC, "tile_body.h"),
-           os.path.join(os.path.dirname(HERE), "include", "infercept_hot.h")]
+           os.path.join(os.path.dirname(HERE), "include", "infercept_hot.h"),
+           os.path.join(os.path.dirname(HERE), "include", "infercept_measure.h")]
 
 # Packed-fp32 VALU forms are disabled on purpose (hipcc only; the host pass warns and ignores it).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

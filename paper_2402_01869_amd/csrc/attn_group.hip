@@ -250,16 +250,17 @@ __global__ __launch_bounds__(64 * kGroupWaves, (D <= 128 ? 2 : 1)) void group_at
   const uint32_t wg = blockIdx.x;
   const int item_idx = wg / Hk;
   const int kvh = wg - item_idx * Hk;
-  const RowItem it = p.row_items[item_idx];
+  const RowItem it = p.row_items[p.n_vec_items + item_idx];  // the group kernel's items follow the vector kernel's
   group_body<D>(p, it, kvh, lds);
 }
 
 }  // namespace
 
 hipError_t launch_group_kernel(const AttnParams& p, int head_dim, hipStream_t st) {
-  if (p.n_row_items <= 0) return hipSuccess;
+  const int n_items = p.n_row_items - p.n_vec_items;
+  if (n_items <= 0) return hipSuccess;
   if (p.group < 2 || p.group > 32) return hipErrorInvalidValue;
-  const uint64_t grid = (uint64_t)p.n_row_items * (uint64_t)p.num_kv_heads;
+  const uint64_t grid = (uint64_t)n_items * (uint64_t)p.num_kv_heads;
   if (grid > 0x7fffffffull) return hipErrorInvalidValue;
   const dim3 g((uint32_t)grid), b(64 * kGroupWaves);
   switch (head_dim) {

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(kRowWaves * 64) void row_persist_kernel(AttnParams 
   __shared__ __attribute__((aligned(16))) float lds[row_lds_bytes<D>() / sizeof(float)];
   __shared__ int s_next;
   const int H = p.num_heads;
-  const uint32_t n_r = (uint32_t)p.n_row_items * (uint32_t)H;
+  const uint32_t n_r = (uint32_t)p.n_vec_items * (uint32_t)H;
   for (;;) {
     if (threadIdx.x == 0) s_next = atomicAdd(&p.counters[8], 1);
     __syncthreads();
@@ -68,8 +68,8 @@ __global__ __launch_bounds__(D) void merge_kernel(AttnParams p) {
 }  // namespace
 
 hipError_t launch_row_kernel(const AttnParams& p, int head_dim, hipStream_t st) {
-  if (p.n_row_items <= 0) return hipSuccess;
-  const uint64_t grid = (uint64_t)p.n_row_items * p.num_heads;
+  if (p.n_vec_items <= 0) return hipSuccess;
+  const uint64_t grid = (uint64_t)p.n_vec_items * p.num_heads;
   if (grid > 0x7fffffffull) return hipErrorInvalidValue;
   const dim3 g((uint32_t)grid), b(kRowWaves * 64);
 #define IC_ROW_CASE(DD)                                                                       \
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kRowWaves * 64, 6) void row_persist_slim_kernel(Att
   __shared__ __attribute__((aligned(16))) float lds[row_lds_bytes<D>() / sizeof(float)];
   __shared__ int s_next;
   const int H = p.num_heads;
-  const uint32_t n_r = (uint32_t)p.n_row_items * (uint32_t)H;
+  const uint32_t n_r = (uint32_t)p.n_vec_items * (uint32_t)H;
   for (;;) {
     if (threadIdx.x == 0) s_next = atomicAdd(&p.counters[8], 1);
     __syncthreads();
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kRowWaves * 64, 6) void row_persist_slim_kernel(Att
 }
 
 hipError_t launch_row_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st) {
-  if (p.n_row_items <= 0) return hipSuccess;
+  if (p.n_vec_items <= 0) return hipSuccess;
   if (!p.counters || slots < 1) return hipErrorInvalidValue;
   const dim3 g((uint32_t)slots), b(kRowWaves * 64);
   switch (head_dim) {
@@ -128,7 +128,7 @@ hipError_t launch_row_persist(const AttnParams& p, int head_dim, int slots, hipS
 }
 
 hipError_t launch_row_persist_slim(const AttnParams& p, int head_dim, int slots, hipStream_t st) {
-  if (p.n_row_items <= 0) return hipSuccess;
+  if (p.n_vec_items <= 0) return hipSuccess;
   if (!p.counters || slots < 1) return hipErrorInvalidValue;
   const dim3 g((uint32_t)slots), b(kRowWaves * 64);
   switch (head_dim) {

@@ -2,6 +2,7 @@
 // See include/infercept_hot.h for the contract of every entry point.
 #include <algorithm>
 #include <cstring>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -16,6 +17,10 @@ constexpr int kStagingSlots = 4;       // pinned host buffers cycled by successi
 constexpr int kDefaultRowPart = 2048;  // keys per decode work item (512 for head_dim 256): ~0.5-1 MiB of KV per head
 constexpr int kDefaultSpanPart = 8192; // keys per span-tile work item (partials of 256 rows are costly)
 constexpr int kUnsplitWorkgroups = 1024;  // tile workgroups (4 per CU) from which spans are not split at all
+// Rows that see fewer keys than this stay off the matrix cores.  There the weights are rounded to bf16
+// before the PV product; with a handful of keys a single weight's rounding (2^-9 relative) shows in the
+// output, with dozens the roundings average out.  The vector path keeps the weights in fp32.
+constexpr int kMfmaMinKeys = 64;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -46,6 +51,8 @@ struct ic_pool {
   int next_slot;
   int32_t* dev_ids;
   size_t dev_ids_cap;
+  std::vector<void*> retired_dev;   // id lists that were outgrown: earlier launches may still read them, freed at destroy
+  std::vector<void*> retired_host;  // the same for pinned descriptor buffers
   int num_cus;           // compute units of the pool's device (0 until the first attention call)
   hipStream_t side;      // second stream: the tile kernel runs beside the row kernel
   hipEvent_t ev_fork, ev_join;
@@ -80,7 +87,7 @@ int check_batch(const ic_pool_cfg& cfg, const ic_batch_desc* d, bool trusted) {
   if (!d) return IC_ENULL;
   if (!d->ctx_len || !d->q_len || !d->q_start || !d->block_tables) return IC_ENULL;
   if (d->num_seqs < 1 || d->max_blocks_per_seq < 1 || d->total_q_rows < 1) return IC_EINVAL;
-  if (!(d->scale == d->scale) || d->scale < 0.f || d->scale > 3.0e38f) return IC_EINVAL;
+  if (!(d->scale > 0.f) || d->scale > 3.0e38f) return IC_EINVAL;  // NaN fails the first comparison
   int64_t rows = 0;
   for (int s = 0; s < d->num_seqs; ++s) {
     const int32_t c = d->ctx_len[s], n = d->q_len[s];
@@ -154,6 +161,8 @@ bool destinations_distinct(const ic_pool_cfg& cfg, const int32_t* dst, size_t ro
 struct PlanSizes {
   ic_plan_info info;
   int row_part, span_part, tile_rows;  // tile_rows: QUERY rows per tile item
+  int min_keys;                        // rows that see fewer keys are vector row items whatever their kind
+  int vec_items;                       // row items [0, vec_items) run on the vector kernel, the rest on the group kernel
   int tile_g_shift;                    // log2 of the query heads one tile workgroup serves
   bool spans_as_rows;
   bool decode_as_tiles;                // grouped pools, span_kernel = 2: decode rows as one-row tile items
@@ -178,6 +187,22 @@ struct ic_plan {
 
 namespace {
 
+// Where the rows of one sequence go.  Rows [0, n_few) see fewer than min_keys keys and are vector row
+// items whatever their kind; the rest are row items (vector or group kernel) or tile items.
+struct SeqRoute {
+  int n_few;        // leading rows of the sequence that stay off the matrix cores
+  bool rest_rows;   // the other rows are row items (else: tile items)
+  bool rest_group;  // ... run by the group kernel
+};
+
+SeqRoute route(const PlanSizes& ps, int c, int n) {
+  SeqRoute r;
+  r.n_few = std::min(n, std::max(0, ps.min_keys - 1 - (c - n)));
+  r.rest_rows = n == 1 ? !ps.decode_as_tiles : ps.spans_as_rows;
+  r.rest_group = r.rest_rows && n == 1 && ps.decode_as_group;
+  return r;
+}
+
 void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   std::memset(&ps, 0, sizeof ps);
   // Grouped-query attention: the G = H / Hkv query heads of a group read the same keys.  When G is a
@@ -195,35 +220,40 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
                                          : (pool->cfg.head_dim >= 256 ? kDefaultRowPart / 4 : kDefaultRowPart);
   ps.row_part = std::min(ps.row_part, kMaxRowPart);
   ps.span_part = t.span_part_tokens > 0 ? round64(t.span_part_tokens) : kDefaultSpanPart;
+  ps.min_keys = t.mfma_min_keys > 0 ? std::min(t.mfma_min_keys, 64) : kMfmaMinKeys;  // <= the smallest partition
+  ps.spans_as_rows = (t.span_kernel == 1);  // default: MFMA tiles
+  ps.decode_as_tiles = ps.tile_g_shift > 0 && t.span_kernel == 2;
+  ps.decode_as_group = ps.tile_g_shift > 0 && t.span_kernel == 0;
   if (t.span_part_tokens == 0) {
     // Splitting a span's keys buys parallelism at the price of fp32 partial results for every row
     // and a merge pass (measured on the long-context shape: 7 % of the call).  When the unsplit query
     // tiles already give every CU several workgroups, do not split.
     int64_t tiles = 0;
     for (int s = 0; s < d->num_seqs; ++s)
-      if (d->q_len[s] > 1) tiles += (d->q_len[s] + kTileRows - 1) / kTileRows;
+      if (d->q_len[s] > 1) {
+        const int rest = d->q_len[s] - route(ps, d->ctx_len[s], d->q_len[s]).n_few;
+        tiles += (rest + kTileRows - 1) / kTileRows;
+      }
     const int64_t head_groups = pool->cfg.num_heads >> ps.tile_g_shift;
     if (tiles * head_groups >= kUnsplitWorkgroups) ps.span_part = 1 << 30;
   }
-  ps.spans_as_rows = (t.span_kernel == 1);  // default: MFMA tiles
-  ps.decode_as_tiles = ps.tile_g_shift > 0 && t.span_kernel == 2;
-  ps.decode_as_group = ps.tile_g_shift > 0 && t.span_kernel == 0;
   ic_plan_info& in = ps.info;
   for (int s = 0; s < d->num_seqs; ++s) {
     const int c = d->ctx_len[s], n = d->q_len[s];
     in.table_entries += (c + kBlockSize - 1) / kBlockSize;
-    if (n == 1 ? !ps.decode_as_tiles : ps.spans_as_rows) {
-      if (n == 1) in.decode_rows += 1; else in.span_rows += n;
-      for (int i = 0; i < n; ++i) {
-        const int klen = c - n + i + 1;
-        const int parts = (klen + ps.row_part - 1) / ps.row_part;
-        in.row_items += parts;
-        if (parts > 1) { in.partial_slots += parts; in.merge_rows += 1; }
-      }
-    } else {
-      if (n == 1) in.decode_rows += 1; else in.span_rows += n;
+    if (n == 1) in.decode_rows += 1; else in.span_rows += n;
+    const SeqRoute rt = route(ps, c, n);
+    const int n_as_rows = rt.rest_rows ? n : rt.n_few;
+    for (int i = 0; i < n_as_rows; ++i) {
+      const int klen = c - n + i + 1;
+      const int parts = (klen + ps.row_part - 1) / ps.row_part;
+      in.row_items += parts;
+      if (i < rt.n_few || !rt.rest_group) ps.vec_items += parts;
+      if (parts > 1) { in.partial_slots += parts; in.merge_rows += 1; }
+    }
+    if (!rt.rest_rows) {
       const int part = n == 1 ? ps.row_part : ps.span_part;
-      for (int r0 = 0; r0 < n; r0 += kTileRows) {
+      for (int r0 = rt.n_few; r0 < n; r0 += kTileRows) {
         const int nr = std::min(kTileRows, n - r0);
         const int klen = c - n + r0 + nr;  // keys visible to the tile's last row
         const int parts = (klen + part - 1) / part;
@@ -247,6 +277,7 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   ps.total_bytes = o;
 }
 
+// May throw std::bad_alloc (per-sequence scratch vectors); callers at the ABI catch it.
 void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
   const int kTileRows = ps.tile_rows;
   std::memset(img + ps.off_ctr, 0, sizeof(int32_t) * 16);  // work-queue counters start at zero
@@ -261,7 +292,9 @@ void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
     append_destinations(d, row_dst);
   }
   int64_t nbt = 0;
-  int nrow = 0, ntiles = 0, nmerge = 0, slot = 0;
+  int nvec = 0, ngrp = ps.vec_items;  // vector items first, group-kernel items after them
+  int ntiles = 0, nmerge = 0, slot = 0;
+  std::vector<int> tile_slot0, tile_parts;
   for (int s = 0; s < d->num_seqs; ++s) {
     const int c = d->ctx_len[s], n = d->q_len[s];
     const int nb = (c + kBlockSize - 1) / kBlockSize;
@@ -269,31 +302,35 @@ void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
     std::memcpy(bt_flat + nbt, d->block_tables + (int64_t)s * d->max_blocks_per_seq,
                 sizeof(int32_t) * (size_t)nb);
     nbt += nb;
-    if (n == 1 ? !ps.decode_as_tiles : ps.spans_as_rows) {
-      for (int i = 0; i < n; ++i) {
-        const int klen = c - n + i + 1;
-        const int parts = (klen + ps.row_part - 1) / ps.row_part;
-        const int qrow = d->q_start[s] + i;
-        if (parts > 1) merges[nmerge++] = MergeItem{qrow, slot, parts, 0};
-        for (int k = 0; k < parts; ++k) {
-          RowItem& it = rows[nrow++];
-          it.seq = s;
-          it.qrow = qrow;
-          it.k_begin = k * ps.row_part;
-          it.k_end = std::min(klen, (k + 1) * ps.row_part);
-          it.slot = parts > 1 ? slot++ : -1;
-          it.pad[0] = it.pad[1] = it.pad[2] = 0;
-        }
+    const SeqRoute rt = route(ps, c, n);
+    const int n_as_rows = rt.rest_rows ? n : rt.n_few;
+    for (int i = 0; i < n_as_rows; ++i) {
+      const int klen = c - n + i + 1;
+      const int parts = (klen + ps.row_part - 1) / ps.row_part;
+      const int qrow = d->q_start[s] + i;
+      const bool vec = i < rt.n_few || !rt.rest_group;
+      if (parts > 1) merges[nmerge++] = MergeItem{qrow, slot, parts, 0};
+      for (int k = 0; k < parts; ++k) {
+        RowItem& it = rows[vec ? nvec++ : ngrp++];
+        it.seq = s;
+        it.qrow = qrow;
+        it.k_begin = k * ps.row_part;
+        it.k_end = std::min(klen, (k + 1) * ps.row_part);
+        it.slot = parts > 1 ? slot++ : -1;
+        it.pad[0] = it.pad[1] = it.pad[2] = 0;
       }
-    } else {
+    }
+    if (!rt.rest_rows && rt.n_few < n) {
       // slots first (per tile: rows x partitions), then items ordered partition-major so that the
       // query tiles which read the same keys are dispatched next to each other
-      const int ntile = (n + kTileRows - 1) / kTileRows;
+      const int first = rt.n_few;
+      const int ntile = (n - first + kTileRows - 1) / kTileRows;
       const int part = n == 1 ? ps.row_part : ps.span_part;
       int max_parts = 0;
-      std::vector<int> tile_slot0((size_t)ntile, -1), tile_parts((size_t)ntile, 0);
+      tile_slot0.assign((size_t)ntile, -1);
+      tile_parts.assign((size_t)ntile, 0);
       for (int ti = 0; ti < ntile; ++ti) {
-        const int r0 = ti * kTileRows;
+        const int r0 = first + ti * kTileRows;
         const int nr = std::min(kTileRows, n - r0);
         const int klen = c - n + r0 + nr;
         const int parts = (klen + part - 1) / part;
@@ -309,7 +346,7 @@ void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
       for (int k = 0; k < max_parts; ++k)
         for (int ti = 0; ti < ntile; ++ti) {
           if (k >= tile_parts[ti]) continue;
-          const int r0 = ti * kTileRows;
+          const int r0 = first + ti * kTileRows;
           const int nr = std::min(kTileRows, n - r0);
           const int pos0 = c - n + r0;
           const int klen = pos0 + nr;
@@ -345,6 +382,17 @@ hipStream_t shared_side_stream() {
   return side[dev];
 }
 
+// Sizes of the pool's own buffers, fixed at the first GPU call from the pool's shape so that later calls
+// allocate nothing: a descriptor image is block tables (at most one entry per block while sequences
+// share none), work items and one int per query row; an id list is at most one entry per block (a
+// swap) or per cache slot (an append).  Only a call beyond these sizes grows a buffer, and then the
+// old one is kept until kv_pool_destroy (launches in flight may still read it) instead of being
+// freed behind a device-wide wait.
+size_t pinned_slot_bytes(const ic_pool* pool) { return align_up(((size_t)256 << 10) + 8 * (size_t)pool->cfg.num_blocks, 4096); }
+size_t dev_ids_bytes(const ic_pool* pool) {
+  return align_up(std::max((size_t)1 << 16, sizeof(int32_t) * (size_t)kBlockSize * (size_t)pool->cfg.num_blocks), 4096);
+}
+
 int acquire_slot(ic_pool* pool, size_t bytes, StagingSlot** out) {
   StagingSlot& s = pool->slots[pool->next_slot];
   pool->next_slot = (pool->next_slot + 1) % kStagingSlots;
@@ -354,11 +402,11 @@ int acquire_slot(ic_pool* pool, size_t bytes, StagingSlot** out) {
   }
   if (!s.ev && hipEventCreateWithFlags(&s.ev, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
   if (s.cap < bytes) {
-    if (s.host) (void)hipHostFree(s.host);
-    s.host = nullptr;
-    s.cap = 0;
-    const size_t cap = align_up(std::max(bytes, (size_t)1 << 16), 4096);
-    if (hipHostMalloc(&s.host, cap, hipHostMallocDefault) != hipSuccess) return IC_EHIP;
+    const size_t cap = std::max(align_up(bytes, 4096), pinned_slot_bytes(pool));
+    void* fresh = nullptr;
+    if (hipHostMalloc(&fresh, cap, hipHostMallocDefault) != hipSuccess) return IC_EHIP;
+    if (s.host) pool->retired_host.push_back(s.host);
+    s.host = fresh;
     s.cap = cap;
   }
   *out = &s;
@@ -383,6 +431,18 @@ struct ProfScope {
 };
 
 bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+// Nothing may be thrown through the C ABI: the host-side checks and the planner use std::vector.
+template <class F>
+int guarded(F&& body) noexcept {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return IC_ENOMEM;
+  } catch (...) {
+    return IC_EINVAL;
+  }
+}
 
 }  // namespace
 
@@ -440,6 +500,8 @@ int kv_pool_destroy(ic_pool* pool) {
   }
   for (hipEvent_t e : pool->prof.ev) (void)hipEventDestroy(e);
   if (pool->dev_ids) (void)hipFree(pool->dev_ids);
+  for (void* p : pool->retired_dev) (void)hipFree(p);
+  for (void* p : pool->retired_host) (void)hipHostFree(p);
   if (pool->side && hipStreamSynchronize(pool->side) != hipSuccess) rc = IC_EHIP;  // shared: never destroyed
   if (pool->ev_fork) (void)hipEventDestroy(pool->ev_fork);
   if (pool->ev_join) (void)hipEventDestroy(pool->ev_join);
@@ -452,13 +514,13 @@ size_t kv_block_bytes(const ic_pool* pool) { return pool ? pool->block_bytes : 0
 int ic_check_batch(const ic_pool_cfg* cfg, const ic_batch_desc* desc) {
   const int rc = check_cfg(cfg);
   if (rc != IC_OK) return rc;
-  return check_batch(*cfg, desc, false);
+  return guarded([&] { return check_batch(*cfg, desc, false); });
 }
 
 int ic_check_ids(const ic_pool_cfg* cfg, const int32_t* host_ids, int32_t n, int require_distinct) {
   const int rc = check_cfg(cfg);
   if (rc != IC_OK) return rc;
-  return check_ids(*cfg, host_ids, n, require_distinct != 0);
+  return guarded([&] { return check_ids(*cfg, host_ids, n, require_distinct != 0); });
 }
 
 int ic_pool_set_tuning(ic_pool* pool, const ic_tuning* tuning) {
@@ -466,7 +528,8 @@ int ic_pool_set_tuning(ic_pool* pool, const ic_tuning* tuning) {
   if (tuning->decode_part_tokens < 0 || tuning->span_part_tokens < 0 || tuning->span_kernel < 0 ||
       tuning->span_kernel > 2 || tuning->row_variant < 0 || tuning->row_variant > 3 ||
       tuning->serial_spans < 0 || tuning->serial_spans > 1 || tuning->row_launch < 0 || tuning->row_launch > 3 ||
-      tuning->row_slots < 0 || tuning->row_slots > 65536 || tuning->reserved[0])
+      tuning->row_slots < 0 || tuning->row_slots > 65536 || tuning->mfma_min_keys < 0 ||
+      tuning->mfma_min_keys > 64 || tuning->reserved[0])
     return IC_EINVAL;
   pool->tune = *tuning;
   return IC_OK;
@@ -485,6 +548,7 @@ int ic_plan_query(const ic_pool* pool, const ic_batch_desc* desc, ic_plan_info* 
 int ic_plan_image(const ic_pool* pool, const ic_batch_desc* desc, void* host_image, size_t host_bytes,
                   ic_plan_layout* out) {
   if (!pool || !desc || !out) return IC_ENULL;
+  return guarded([&]() -> int {
   const int rc = check_batch(pool->cfg, desc, false);
   if (rc != IC_OK) return rc;
   PlanSizes ps;
@@ -505,12 +569,14 @@ int ic_plan_image(const ic_pool* pool, const ic_batch_desc* desc, void* host_ima
   out->n_row_items = ps.info.row_items;
   out->n_tile_items = ps.info.tile_items;
   out->n_merge_items = ps.info.merge_rows;
+  out->n_vector_row_items = ps.vec_items;
   if (host_image) {
     if (host_bytes < ps.image_bytes) return IC_ESIZE;
     std::memset(host_image, 0, ps.image_bytes);
     plan_fill(desc, ps, (char*)host_image);
   }
   return IC_OK;
+  });
 }
 
 size_t paged_attn_mixed_workspace_bytes(const ic_pool* pool, const ic_batch_desc* desc) {
@@ -563,6 +629,7 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
   p.group = pool->cfg.num_heads / pool->cfg.num_kv_heads;
   p.tile_g_shift = ps.tile_g_shift;
   p.n_row_items = ps.info.row_items;
+  p.n_vec_items = ps.vec_items;
   p.n_tile_items = ps.info.tile_items;
   p.n_merge_items = ps.info.merge_rows;
   p.scale_log2e = scale * 1.4426950408889634f;
@@ -576,7 +643,7 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
   // workgroup leaves no registers for a neighbour), run one kernel after the other instead.
   // Grouped pools run the tile kernel, then the group kernel (measured: as two ordinary launches on
   // two streams they overlap by 2 %, not worth a second queue).
-  const bool beside = p.n_tile_items > 0 && p.n_row_items > 0 && !pool->tune.serial_spans && D <= 128 &&
+  const bool beside = p.n_tile_items > 0 && p.n_vec_items > 0 && !pool->tune.serial_spans && D <= 128 &&
                       !ps.decode_as_group;
   if (beside) {
     if (!pool->side) {  // the stream is assigned last: a half-made set is retried by the next call
@@ -586,25 +653,33 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
     }
     if (hipEventRecord(pool->ev_fork, st) != hipSuccess) return IC_EHIP;
     if (hipStreamWaitEvent(pool->side, pool->ev_fork, 0) != hipSuccess) return IC_EHIP;
+    // From here on the side stream may hold work that writes dev_out and the workspace: whatever fails
+    // below, the caller's stream is still made to wait for it (or, failing that, the host does).
+    bool ok = true;
     {
       ProfScope ps_(pool, IC_K_TILE, pool->side);
-      if (launch_tile_persist(p, D, pool->num_cus, pool->side) != hipSuccess) return IC_EHIP;
+      ok = launch_tile_persist(p, D, pool->num_cus, pool->side) == hipSuccess;
     }
-    if (hipEventRecord(pool->ev_join, pool->side) != hipSuccess) return IC_EHIP;
-    {
+    const bool joined = hipEventRecord(pool->ev_join, pool->side) == hipSuccess;
+    if (ok) {
       ProfScope ps_(pool, IC_K_ROW, st);
-      if (launch_row_persist_slim(p, D, pool->num_cus, st) != hipSuccess) return IC_EHIP;
+      ok = launch_row_persist_slim(p, D, pool->num_cus, st) == hipSuccess;
     }
-    if (hipStreamWaitEvent(st, pool->ev_join, 0) != hipSuccess) return IC_EHIP;
+    if (!joined || hipStreamWaitEvent(st, pool->ev_join, 0) != hipSuccess) {
+      (void)hipStreamSynchronize(pool->side);
+      return IC_EHIP;
+    }
+    if (!ok) return IC_EHIP;
   } else {
     if (p.n_tile_items > 0) {
       ProfScope ps_(pool, IC_K_TILE, st);
       if (launch_tile_kernel(p, D, st) != hipSuccess) return IC_EHIP;
     }
-    if (p.n_row_items > 0 && ps.decode_as_group) {
-      ProfScope ps_(pool, IC_K_ROW, st);
+    if (p.n_row_items > p.n_vec_items) {
+      ProfScope ps_(pool, IC_K_GROUP, st);
       if (launch_group_kernel(p, D, st) != hipSuccess) return IC_EHIP;
-    } else if (p.n_row_items > 0) {
+    }
+    if (p.n_vec_items > 0) {
       ProfScope ps_(pool, IC_K_ROW, st);
       const int slots = pool->tune.row_slots > 0 ? pool->tune.row_slots : pool->num_cus;
       const hipError_t e = pool->tune.row_launch == 3 && D <= 128 ? launch_row_persist_slim(p, D, slots, st)
@@ -624,31 +699,30 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
 int paged_attn_mixed(ic_pool* pool, const ic_batch_desc* desc, const void* dev_q, void* dev_out,
                      void* dev_workspace, size_t workspace_bytes, void* hip_stream) {
   if (!pool || !desc || !dev_q || !dev_out || !dev_workspace) return IC_ENULL;
-  int rc = check_batch(pool->cfg, desc, (desc->flags & IC_FLAG_TRUSTED) != 0);
-  if (rc != IC_OK) return rc;
-  if (misaligned(dev_q) || misaligned(dev_out) || ((uintptr_t)dev_workspace & 255u)) return IC_EALIGN;
-  PlanSizes ps;
-  plan_sizes(pool, desc, ps);
-  if (workspace_bytes < ps.total_bytes) return IC_ESIZE;
-  hipStream_t st = (hipStream_t)hip_stream;
-  char* ws = (char*)dev_workspace;
-  if ((rc = upload_plan(pool, desc, ps, ws, st)) != IC_OK) return rc;
-  return launch_attention(pool, ps, desc->scale, dev_q, dev_out, ws, st);
+  return guarded([&]() -> int {
+    int rc = check_batch(pool->cfg, desc, (desc->flags & IC_FLAG_TRUSTED) != 0);
+    if (rc != IC_OK) return rc;
+    if (misaligned(dev_q) || misaligned(dev_out) || ((uintptr_t)dev_workspace & 255u)) return IC_EALIGN;
+    PlanSizes ps;
+    plan_sizes(pool, desc, ps);
+    if (workspace_bytes < ps.total_bytes) return IC_ESIZE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* ws = (char*)dev_workspace;
+    if ((rc = upload_plan(pool, desc, ps, ws, st)) != IC_OK) return rc;
+    return launch_attention(pool, ps, desc->scale, dev_q, dev_out, ws, st);
+  });
 }
 
 int paged_attn_plan_create(ic_pool* pool, const ic_batch_desc* desc, void* dev_workspace, size_t workspace_bytes,
                            void* hip_stream, ic_plan** out) {
   if (!pool || !desc || !dev_workspace || !out) return IC_ENULL;
+  return guarded([&]() -> int {
   int rc = check_batch(pool->cfg, desc, (desc->flags & IC_FLAG_TRUSTED) != 0);
   if (rc != IC_OK) return rc;
   if ((uintptr_t)dev_workspace & 255u) return IC_EALIGN;
-  ic_plan* pl = new (std::nothrow) ic_plan();
-  if (!pl) return IC_ENOMEM;
+  std::unique_ptr<ic_plan> pl(new ic_plan());
   plan_sizes(pool, desc, pl->ps);
-  if (workspace_bytes < pl->ps.total_bytes) {
-    delete pl;
-    return IC_ESIZE;
-  }
+  if (workspace_bytes < pl->ps.total_bytes) return IC_ESIZE;
   pl->cfg = pool->cfg;
   pl->tune = pool->tune;
   pl->scale = desc->scale;
@@ -660,12 +734,10 @@ int paged_attn_plan_create(ic_pool* pool, const ic_batch_desc* desc, void* dev_w
     append_destinations(desc, dst.data());
     pl->append_checked = destinations_distinct(pool->cfg, dst.data(), dst.size());
   }
-  if ((rc = upload_plan(pool, desc, pl->ps, pl->ws, (hipStream_t)hip_stream)) != IC_OK) {
-    delete pl;
-    return rc;
-  }
-  *out = pl;
+  if ((rc = upload_plan(pool, desc, pl->ps, pl->ws, (hipStream_t)hip_stream)) != IC_OK) return rc;
+  *out = pl.release();
   return IC_OK;
+  });
 }
 
 int paged_attn_planned(ic_pool* pool, const ic_plan* plan, const void* dev_q, void* dev_out, void* hip_stream) {
@@ -704,15 +776,11 @@ int paged_attn_plan_destroy(ic_plan* plan) {
 // The pool's device-side int32 list (block ids of a swap, row destinations of an append).
 static int ensure_dev_ids(ic_pool* pool, size_t bytes) {
   if (pool->dev_ids_cap >= bytes) return IC_OK;
-  // Growing the buffer: earlier launches may still read the old one.
-  if (pool->dev_ids) {
-    if (hipDeviceSynchronize() != hipSuccess) return IC_EHIP;
-    (void)hipFree(pool->dev_ids);
-    pool->dev_ids = nullptr;
-    pool->dev_ids_cap = 0;
-  }
-  const size_t cap = align_up(std::max(bytes, (size_t)1 << 16), 4096);
-  if (hipMalloc((void**)&pool->dev_ids, cap) != hipSuccess) return IC_EHIP;
+  const size_t cap = std::max(align_up(bytes, 4096), dev_ids_bytes(pool));
+  int32_t* fresh = nullptr;
+  if (hipMalloc((void**)&fresh, cap) != hipSuccess) return IC_EHIP;
+  if (pool->dev_ids) pool->retired_dev.push_back(pool->dev_ids);  // earlier launches may still read it
+  pool->dev_ids = fresh;
   pool->dev_ids_cap = cap;
   return IC_OK;
 }
@@ -723,6 +791,7 @@ static int swap_common(ic_pool* pool, const int32_t* host_ids, int32_t n, const 
   if (n < 0) return IC_EINVAL;
   if (n == 0) return IC_OK;
   if (!host_ids || !dev_staging) return IC_ENULL;
+  return guarded([&]() -> int {
   int rc = check_ids(pool->cfg, host_ids, n, !pack);
   if (rc != IC_OK) return rc;
   if (misaligned(dev_staging)) return IC_EALIGN;
@@ -753,6 +822,7 @@ static int swap_common(ic_pool* pool, const int32_t* host_ids, int32_t n, const 
              : launch_unpack(pool->base, dev_staging, pool->dev_ids, n, pool->block_bytes, st);
   }
   return e == hipSuccess ? IC_OK : IC_EHIP;
+  });
 }
 
 int kv_pack_blocks(ic_pool* pool, const int32_t* host_ids, int32_t n, void* dev_staging,
@@ -768,6 +838,7 @@ int kv_unpack_blocks(ic_pool* pool, const int32_t* host_ids, int32_t n, const vo
 int kv_write_span(ic_pool* pool, const ic_batch_desc* desc, const void* dev_k_new, const void* dev_v_new,
                   void* hip_stream) {
   if (!pool || !desc || !dev_k_new || !dev_v_new) return IC_ENULL;
+  return guarded([&]() -> int {
   const bool trusted = (desc->flags & IC_FLAG_TRUSTED) != 0;
   int rc = check_batch(pool->cfg, desc, trusted);
   if (rc != IC_OK) return rc;
@@ -795,21 +866,25 @@ int kv_write_span(ic_pool* pool, const ic_batch_desc* desc, const void* dev_k_ne
                       pool->cfg.head_dim, st);
   }
   return e == hipSuccess ? IC_OK : IC_EHIP;
+  });
 }
 
 int ic_prof_begin(ic_pool* pool, int32_t max_launches) {
   if (!pool) return IC_ENULL;
   if (max_launches < 1 || max_launches > (1 << 20)) return IC_EINVAL;
-  ProfState& pr = pool->prof;
-  while (pr.ev.size() < (size_t)max_launches * 2) {
-    hipEvent_t e;
-    if (hipEventCreate(&e) != hipSuccess) return IC_EHIP;
-    pr.ev.push_back(e);
-  }
-  pr.kind.assign(pr.ev.size() / 2, 0);
-  pr.used = 0;
-  pr.on = true;
-  return IC_OK;
+  return guarded([&]() -> int {
+    ProfState& pr = pool->prof;
+    pr.ev.reserve((size_t)max_launches * 2);
+    while (pr.ev.size() < (size_t)max_launches * 2) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return IC_EHIP;
+      pr.ev.push_back(e);
+    }
+    pr.kind.assign(pr.ev.size() / 2, 0);
+    pr.used = 0;
+    pr.on = true;
+    return IC_OK;
+  });
 }
 
 int ic_prof_end(ic_pool* pool, ic_prof_stats* out) {

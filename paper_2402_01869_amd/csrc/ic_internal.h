@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "../../include/infercept_hot.h"
+#include "../../include/infercept_measure.h"
 
 namespace ic {
 
@@ -75,6 +76,7 @@ struct AttnParams {
   int32_t tile_g_shift;    // log2 of the query heads one tile workgroup serves (they share K/V): a tile's
                            // row r is query row r >> shift, head (first head of the workgroup) + (r & mask)
   int32_t n_row_items;
+  int32_t n_vec_items;     // row items [0, n_vec_items) belong to the vector row kernel, the rest to the group kernel
   int32_t n_tile_items;
   int32_t n_merge_items;
   float scale_log2e;       // scale * log2(e): scores are kept in log2 units

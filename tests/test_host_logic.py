@@ -14,19 +14,24 @@ from paper_2402_01869_amd import workloads as W
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "infercept_hot.h")).read()
+def _declared_functions(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)))
 
 
 def test_library_exports_every_declared_symbol():
-    names = _declared_functions()
-    assert {"kv_pool_init", "paged_attn_mixed", "kv_pack_blocks", "kv_unpack_blocks"} <= set(names)
+    """infercept_hot.h is the method's contract, infercept_measure.h holds the measurement aids; together they
+    declare exactly what the library exports and the binding lists."""
+    method, measure = _declared_functions("infercept_hot.h"), _declared_functions("infercept_measure.h")
+    assert {"kv_pool_init", "paged_attn_mixed", "kv_pack_blocks", "kv_unpack_blocks"} <= set(method)
+    assert set(measure) == {"ic_prof_begin", "ic_prof_end", "ic_mfma_ceiling", "ic_hbm_ceiling", "ic_paged_read_ceiling"}
+    assert not set(method) & set(measure)
+    assert not [n for n in method if "ceiling" in n or "prof" in n]
     raw = C.CDLL(B.LIB_PATH)
-    for n in names:
-        assert hasattr(raw, n), f"{n} declared in the header but not exported"
-    assert set(names) == set(B.EXPORTS), "binding.EXPORTS out of sync with the header"
+    for n in method + measure:
+        assert hasattr(raw, n), f"{n} declared in a header but not exported"
+    assert set(method + measure) == set(B.EXPORTS), "binding.EXPORTS out of sync with the headers"
 
 
 def test_strerror_covers_codes():
@@ -92,6 +97,8 @@ def test_check_batch_codes():
     assert B.check_batch(cfg, desc(block_tables=b.block_tables[:, :2])) == B.IC_ESIZE
     assert B.check_batch(cfg, desc(scale=float("nan"))) == B.IC_EINVAL
     assert B.check_batch(cfg, desc(scale=-1.0)) == B.IC_EINVAL
+    assert B.check_batch(cfg, desc(scale=0.0)) == B.IC_EINVAL      # the kernels need a positive factor
+    assert B.check_batch(cfg, desc(scale=float("inf"))) == B.IC_EINVAL
     # rows may leave gaps in the packed array
     assert B.check_batch(cfg, desc(total_q_rows=b.total_q_rows + 5)) == B.IC_OK
 
@@ -112,15 +119,21 @@ def test_plan_counts_and_workspace():
     d = B.HostDesc.from_batch(b)
     base = p.plan_query(d)
     assert base["decode_rows"] == 2 and base["span_rows"] == int(b.q_len[2:].sum())
-    assert base["row_items"] == 2 and base["partial_slots"] == 0 and base["merge_rows"] == 0
-    assert base["tile_items"] == 2            # one tile per 32-row span, contexts <= 128 keys
+    # rows of a span that see fewer than 64 keys are vector row items; the rest of the span is one tile
+    few = [min(int(n), max(0, 63 - int(c - n))) for c, n in zip(b.ctx_len[2:], b.q_len[2:])]
+    assert base["row_items"] == 2 + sum(few) and base["partial_slots"] == 0 and base["merge_rows"] == 0
+    assert base["tile_items"] == sum(1 for f, n in zip(few, b.q_len[2:]) if f < n)
+    p.set_tuning(mfma_min_keys=1)             # no such routing: every span row on the matrix cores
+    alltile = p.plan_query(d)
+    assert alltile["row_items"] == 2 and alltile["tile_items"] == 2   # one tile per 32-row span
+    p.set_tuning()
     assert base["table_entries"] == int(sum(-(-int(c) // 16) for c in b.ctx_len))
     w0 = p.workspace_bytes(d)
     assert w0 > 0 and w0 % 256 == 0
     # forcing 64-key partitions splits every context longer than 64 keys
     p.set_tuning(64, 64, 0)
     split = p.plan_query(d)
-    want_row_items = sum(-(-int(c) // 64) for c in b.ctx_len[:2])
+    want_row_items = sum(-(-int(c) // 64) for c in b.ctx_len[:2]) + sum(few)
     assert split["row_items"] == want_row_items
     assert split["partial_slots"] > 0 and split["merge_rows"] > 0
     assert p.workspace_bytes(d) > w0
@@ -132,6 +145,8 @@ def test_plan_counts_and_workspace():
         p.set_tuning(-1, 0, 0)
     with pytest.raises(B.InferceptError):
         p.set_tuning(0, 0, 3)
+    with pytest.raises(B.InferceptError):
+        p.set_tuning(mfma_min_keys=65)
     bad = B.HostDesc(b.ctx_len, b.q_len + 1000, b.q_start, b.block_tables, b.scale)
     assert p.workspace_bytes(bad) == 0
     p.close()
@@ -241,9 +256,10 @@ def test_kv_write_span_validation_happens_before_any_gpu_work():
 # Waste model, chunk sizing, saturation point and interception schedule against the oracle
 # ---------------------------------------------------------------------------------------------
 def _close(a, b):
+    """Library and oracle evaluate the same fp64 expressions in the same order: the doubles must be identical."""
     if math.isnan(a) or math.isnan(b):
         return math.isnan(a) and math.isnan(b)
-    return math.isclose(a, b, rel_tol=1e-13, abs_tol=0.0)
+    return a == b
 
 
 def test_waste_model_matches_the_oracle():
@@ -349,7 +365,7 @@ def test_mfma_ceiling_rejects_bad_arguments_before_any_launch():
     assert B.mfma_ceiling(ok_ops + 8, B.IC_CEILING_OPERAND_BYTES, ok_sink, B.IC_CEILING_SINK_BYTES, 10)[0] == B.IC_EALIGN
 
 
-def _check_plan_covers_every_row_once(pool, batch, desc):
+def _check_plan_covers_every_row_once(pool, batch, desc, min_keys=64):
     """Every (query row, visible key) pair is handled by exactly one work item; partial slots are distinct and every
     split row has a merge item naming them; tables, row destinations and alignment are as the kernels assume."""
     P = pool.plan_image(desc)
@@ -372,13 +388,19 @@ def _check_plan_covers_every_row_once(pool, batch, desc):
             want_dst[r0 + i] = int(batch.block_tables[s, t // 16]) * 16 + t % 16
     assert np.array_equal(P["row_dst"], want_dst)
     ranges = [[] for _ in range(rows)]             # per row: (k_begin, k_end_visible, slot)
-    row_of_seq = {}
-    for seq, qrow, kb, ke, slot, p0, p1, p2 in P["row_items"].tolist():
+    n_vec = P["n_vector_row_items"]
+    assert 0 <= n_vec <= P["n_row_items"]
+    if batch.kv_heads == batch.num_heads:
+        assert n_vec == P["n_row_items"]           # only grouped pools have a group kernel
+    for idx, (seq, qrow, kb, ke, slot, p0, p1, p2) in enumerate(P["row_items"].tolist()):
         assert kb % 16 == 0 and 0 <= kb < ke <= klen[qrow] and ke - kb <= P["row_part_tokens"] and p0 == p1 == p2 == 0
         assert batch.q_start[seq] <= qrow < batch.q_start[seq] + batch.q_len[seq]
+        if idx >= n_vec:                           # matrix-core decode rows: never a row of a handful of keys
+            assert klen[qrow] >= min_keys and batch.q_len[seq] == 1
         ranges[qrow].append((kb, ke, slot))
     for seq, qrow0, n_rows, pos0, kb, ke, slot0, nparts in P["tile_items"].tolist():
         assert kb % 64 == 0 and 1 <= n_rows <= P["tile_query_rows"] and nparts >= 1
+        assert pos0 + 1 >= min_keys                # the tile's first row already sees min_keys keys
         assert pos0 == int(batch.ctx_len[seq] - batch.q_len[seq]) + (qrow0 - int(batch.q_start[seq]))
         part = P["row_part_tokens"] if batch.q_len[seq] == 1 else P["span_part_tokens"]   # decode rows as one-row tiles
         assert kb < ke <= pos0 + n_rows and ke - kb <= part
@@ -434,9 +456,10 @@ def test_launch_plan_covers_every_row_and_key_exactly_once(H, Hkv, D):
         pool = B.KvPool(cfg, 0x10000, 2048 * 16 * 2 * Hkv * D * 2)   # the base address is never dereferenced here
         desc = B.HostDesc(batch.ctx_len, batch.q_len, batch.q_start, batch.block_tables, batch.scale, total)
         for tn in (dict(), dict(decode_part_tokens=64, span_part_tokens=64), dict(span_kernel=1, decode_part_tokens=128),
-                   dict(span_kernel=2, decode_part_tokens=256, span_part_tokens=128), dict(span_part_tokens=1 << 20)):
+                   dict(span_kernel=2, decode_part_tokens=256, span_part_tokens=128), dict(span_part_tokens=1 << 20),
+                   dict(mfma_min_keys=1), dict(mfma_min_keys=17, span_kernel=2, decode_part_tokens=64)):
             pool.set_tuning(**tn)
-            _check_plan_covers_every_row_once(pool, batch, desc)
+            _check_plan_covers_every_row_once(pool, batch, desc, tn.get("mfma_min_keys", 64))
         pool.close()
 
 
