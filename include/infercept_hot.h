@@ -39,7 +39,8 @@ enum {
   IC_EUNSUPPORTED = -7, /* dtype, layout, head_dim, block size ... not built            */
   IC_EOVERLAP = -8,     /* query-row ranges of two sequences overlap or leave [0,total) */
   IC_EHIP = -9,         /* the HIP runtime reported an error                            */
-  IC_ENOMEM = -10       /* host allocation failed                                       */
+  IC_ENOMEM = -10,      /* host allocation failed                                       */
+  IC_ELIMIT = -11       /* more than the fixed capacity of an allocation-free entry point */
 };
 
 /* Human-readable text for a return code (static storage, never NULL). */
@@ -248,6 +249,24 @@ int kv_pack_blocks(ic_pool* pool, const int32_t* host_ids, int32_t n, void* dev_
                    size_t staging_bytes, void* hip_stream);
 int kv_unpack_blocks(ic_pool* pool, const int32_t* host_ids, int32_t n, const void* dev_staging,
                      size_t staging_bytes, void* hip_stream);
+
+/*
+ * kv_pack_blocks for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same result, same checks (byte-exact; the staging
+ * buffer is still the caller's).  What differs is where the device-side copy of the id list lives:
+ * kv_pack_blocks keeps it in a buffer the library allocates and uploads it through pinned host
+ * memory it allocates; this call keeps it in a fixed array inside the library's device image
+ * (IC_STATIC_PACK_MAX_BLOCKS ints = 256 KiB on every GPU the library runs on, held until the process
+ * ends) and sends the ids as kernel arguments, 960 per launch, ahead of the one gather launch.  It
+ * calls no allocating routine of the HIP runtime or of any library, and touches no pool-owned buffer.
+ * n > IC_STATIC_PACK_MAX_BLOCKS gives IC_ELIMIT (split the list, or use kv_pack_blocks).
+ * Every call on one GPU uses that GPU's one array: calls ordered on one stream are safe (the array
+ * is rewritten for each call, nothing of the previous list survives), calls that overlap on
+ * different streams of one GPU race.
+ */
+#define IC_STATIC_PACK_MAX_BLOCKS 65536
+int kv_pack_blocks_static(ic_pool* pool, const int32_t* host_ids, int32_t n, void* dev_staging,
+                          size_t staging_bytes, void* hip_stream);
 
 /* Host-only validation of an id list: range, and distinctness when require_distinct != 0. */
 int ic_check_ids(const ic_pool_cfg* cfg, const int32_t* host_ids, int32_t n, int require_distinct);

@@ -17,7 +17,8 @@ LIB_PATH = os.environ.get("INFERCEPT_HOT_LIB") or os.path.join(_HERE, "libinferc
 
 IC_OK = 0
 IC_ENULL, IC_EINVAL, IC_ERANGE, IC_ESIZE, IC_EALIGN = -1, -2, -3, -4, -5
-IC_EDUP, IC_EUNSUPPORTED, IC_EOVERLAP, IC_EHIP, IC_ENOMEM = -6, -7, -8, -9, -10
+IC_EDUP, IC_EUNSUPPORTED, IC_EOVERLAP, IC_EHIP, IC_ENOMEM, IC_ELIMIT = -6, -7, -8, -9, -10, -11
+IC_STATIC_PACK_MAX_BLOCKS = 65536
 IC_FLAG_TRUSTED = 1
 IC_K_ROW, IC_K_TILE, IC_K_MERGE, IC_K_PACK, IC_K_UNPACK, IC_K_UPLOAD, IC_K_APPEND, IC_K_GROUP, IC_K_COUNT = range(9)
 KERNEL_NAMES = ("row", "tile", "merge", "pack", "unpack", "upload", "append", "group")
@@ -33,7 +34,7 @@ EXPORTS = (
     "ic_tfwd_eval", "ic_waste_discard", "ic_waste_preserve", "ic_waste_swap", "ic_waste_chunked_discard",
     "ic_chunk_tokens", "ic_chunk_count", "ic_saturation_point", "ic_schedule_intercepted",
     "paged_attn_plan_create", "paged_attn_planned", "paged_attn_plan_destroy", "kv_write_span_planned",
-    "ic_mfma_ceiling", "ic_plan_image", "ic_hbm_ceiling", "ic_paged_read_ceiling",
+    "ic_mfma_ceiling", "ic_plan_image", "ic_hbm_ceiling", "ic_paged_read_ceiling", "kv_pack_blocks_static",
 )
 IC_CEILING_OPERAND_BYTES = 1 << 20
 IC_CEILING_SINK_BYTES = 256 * 512 * 4 + 256 * 16
@@ -132,6 +133,7 @@ def lib():
         L.ic_plan_query.argtypes = [vp, C.POINTER(BatchDesc), C.POINTER(PlanInfo)]
         L.kv_pack_blocks.argtypes = [vp, i32p, C.c_int32, vp, C.c_size_t, vp]
         L.kv_unpack_blocks.argtypes = [vp, i32p, C.c_int32, vp, C.c_size_t, vp]
+        L.kv_pack_blocks_static.argtypes = [vp, i32p, C.c_int32, vp, C.c_size_t, vp]
         L.ic_check_ids.argtypes = [C.POINTER(PoolCfg), i32p, C.c_int32, C.c_int]
         L.ic_prof_begin.argtypes = [vp, C.c_int32]
         L.ic_prof_end.argtypes = [vp, C.POINTER(ProfStats)]
@@ -346,6 +348,15 @@ class KvPool:
                                   int(staging_bytes), C.c_void_p(stream))
         if check and rc != IC_OK:
             raise InferceptError(rc, "kv_pack_blocks")
+        return int(rc)
+
+    def kv_pack_blocks_static(self, ids, staging_ptr: int, staging_bytes: int, stream: int = 0, check: bool = True) -> int:
+        """kv_pack_blocks without any allocation: the id list goes to a fixed array in the library's device image."""
+        ids = _i32(ids)
+        rc = lib().kv_pack_blocks_static(self._h, _ptr(ids), int(ids.shape[0]), C.c_void_p(staging_ptr),
+                                         int(staging_bytes), C.c_void_p(stream))
+        if check and rc != IC_OK:
+            raise InferceptError(rc, "kv_pack_blocks_static")
         return int(rc)
 
     def kv_unpack_blocks(self, ids, staging_ptr: int, staging_bytes: int, stream: int = 0, check: bool = True) -> int:

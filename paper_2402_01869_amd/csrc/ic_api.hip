@@ -462,6 +462,7 @@ const char* ic_strerror(int code) {
     case IC_EOVERLAP: return "query-row ranges overlap or leave the packed array";
     case IC_EHIP: return "HIP runtime error";
     case IC_ENOMEM: return "host allocation failed";
+    case IC_ELIMIT: return "more than the fixed capacity of this allocation-free entry point";
     default: return "unknown error code";
   }
 }

@@ -4,6 +4,9 @@
 //
 // Pure byte movement, HBM-bound.  Every lane moves 16 bytes with non-temporal loads and stores;
 // the grid is (blocks in the list) x (chunks per block), hundreds of thousands of workgroups.
+#include <cstring>
+#include <mutex>
+
 #include "ic_internal.h"
 
 namespace ic {
@@ -138,6 +141,80 @@ hipError_t launch_upload(void* dev_dst, const void* pinned_src, size_t bytes, hi
                      (const u32x4*)pinned_src, n16);
   return hipGetLastError();
 }
+
+// ---------------------------------------------------------------------------------------------
+// kv_pack_blocks for callers that cannot allocate: the device-side id list, which kv_pack_blocks
+// keeps in a buffer the library allocates, lives in a fixed array of this library's image instead,
+// and the ids travel to it as kernel arguments, so that the call needs no pinned host buffer either.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+static __device__ __align__(256) int32_t scratch[IC_STATIC_PACK_MAX_BLOCKS];  // one copy per GPU, held until the process ends
+
+struct IdChunk {
+  int32_t v[960];  // with the other arguments: under the 4 KiB a launch may carry
+};
+
+__global__ __launch_bounds__(64) void ids_from_args_kernel(IdChunk chunk, int32_t* __restrict__ dst, int32_t count) {
+  const int32_t i = (int32_t)(blockIdx.x * 64u + threadIdx.x);
+  if (i < count) dst[i] = chunk.v[i];
+}
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a handle
+// for hipGetSymbolAddress; every GPU holds its own copy at its own address, looked up once.
+int static_ids(int32_t** out) {
+  static std::mutex mu;
+  static int32_t* ptr[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return IC_EHIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return IC_EHIP;
+    ptr[dev] = (int32_t*)p;
+  }
+  *out = ptr[dev];
+  return IC_OK;
+}
+
+}  // namespace
+
+}  // namespace ic
+
+extern "C" int kv_pack_blocks_static(ic_pool* pool, const int32_t* host_ids, int32_t n, void* dev_staging,
+                                     size_t staging_bytes, void* hip_stream) {
+  using namespace ic;
+  if (!pool) return IC_ENULL;
+  if (n < 0) return IC_EINVAL;
+  if (n == 0) return IC_OK;
+  if (!host_ids || !dev_staging) return IC_ENULL;
+  if (n > IC_STATIC_PACK_MAX_BLOCKS) return IC_ELIMIT;
+  const PoolView pv = pool_view(pool);
+  for (int32_t i = 0; i < n; ++i)
+    if (host_ids[i] < 0 || host_ids[i] >= pv.cfg.num_blocks) return IC_ERANGE;
+  if ((uintptr_t)dev_staging & 15u) return IC_EALIGN;
+  if (staging_bytes / pv.block_bytes < (size_t)n) return IC_ESIZE;
+  {
+    const char* s0 = (const char*)dev_staging;
+    const char* s1 = s0 + (size_t)n * pv.block_bytes;
+    if (s0 < pv.base + pv.bytes && pv.base < s1) return IC_EINVAL;  // staging must not overlap the pool
+  }
+  int32_t* ids = nullptr;
+  const int rc = static_ids(&ids);
+  if (rc != IC_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  IdChunk chunk;
+  constexpr int32_t kPer = (int32_t)(sizeof(chunk.v) / sizeof(chunk.v[0]));
+  for (int32_t off = 0; off < n; off += kPer) {
+    const int32_t count = n - off < kPer ? n - off : kPer;
+    std::memcpy(chunk.v, host_ids + off, sizeof(int32_t) * (size_t)count);
+    hipLaunchKernelGGL(ids_from_args_kernel, dim3((uint32_t)(count + 63) / 64u), dim3(64), 0, st, chunk, ids + off, count);
+    if (hipGetLastError() != hipSuccess) return IC_EHIP;
+  }
+  return launch_pack(pv.base, dev_staging, ids, n, pv.block_bytes, st) == hipSuccess ? IC_OK : IC_EHIP;
+}
+
+namespace ic {
 
 hipError_t launch_pack(const void* pool, void* staging, const int32_t* dev_ids, int32_t n,
                        size_t block_bytes, hipStream_t st) {

@@ -35,8 +35,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_strerror_covers_codes():
-    seen = {B.strerror(c) for c in range(0, -11, -1)}
-    assert len(seen) == 11 and "unknown error code" not in seen
+    seen = {B.strerror(c) for c in range(0, -12, -1)}
+    assert len(seen) == 12 and "unknown error code" not in seen
     assert B.strerror(-99) == "unknown error code"
 
 
