@@ -25,11 +25,12 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
 # profiles/row_persist_kernel_gptj_decode.md, profiles/group_and_tile_kernels_gqa_70b.md and
 # profiles/tile_persist_kernel_long_ctx.md.  Only valid for the
 # default launch plan of these workloads.
-MEASURED_TRAFFIC_BYTES = {"mixed_13b/row": (2837644 * 2.0 + 4263) * 1024,
-                          "gptj_decode/row": (660656 * 2.0 + 3278) * 1024,
-                          "gqa_70b/row": (537675 * 2.0 + 5144) * 1024,
-                          "gqa_70b/tile": (84887 * 2.0 + 65536) * 1024,
-                          "long_ctx/tile": (6133628 * 2.0 + 262292) * 1024}
+MEASURED_TRAFFIC = {"mixed_13b/row": ((2837644 * 2.0 + 4263) * 1024, "profiles/row_and_tile_persist_kernels_mixed_13b.md"),
+                    "gptj_decode/row": ((660656 * 2.0 + 3278) * 1024, "profiles/row_persist_kernel_gptj_decode.md"),
+                    "gqa_70b/group": ((537675 * 2.0 + 5144) * 1024, "profiles/group_and_tile_kernels_gqa_70b.md"),
+                    "gqa_70b/tile": ((84887 * 2.0 + 65536) * 1024, "profiles/group_and_tile_kernels_gqa_70b.md"),
+                    "long_ctx/tile": ((6133628 * 2.0 + 262292) * 1024, "profiles/tile_persist_kernel_long_ctx.md")}
+SWAP_LOOP, SWAP_REPS = 50, 7   # pack / unpack timing: launches per event pair, loops
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
 
@@ -38,7 +39,12 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="mixed_13b", choices=["mixed_13b", "gptj_decode", "long_ctx", "tiny", "gqa_70b"])
+    ap.add_argument("--workload", default="mixed_13b",
+                    choices=["mixed_13b", "gptj_decode", "long_ctx", "tiny", "gqa_70b", "gptj_mixed"])
+    ap.add_argument("--clock-ramp", type=float, default=0.4,
+                    help="seconds of untimed back-to-back steps before the warm-up steps (GPU clocks ramp after an idle gap)")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short timing of the other attention configurations after the main workload")
     ap.add_argument("--decode-part", type=int, default=0)
     ap.add_argument("--span-part", type=int, default=0)
     ap.add_argument("--span-kernel", type=int, default=0)
@@ -390,51 +396,183 @@ def saturation_bench(args):
     print(json.dumps(result))
 
 
+class AttnSetup:
+    """Device inputs of one attention workload: the pool, two batches (different tables and q) that alternate between
+    calls so that no call finds the previous one's keys in the last-level cache, outputs and one workspace."""
+
+    def __init__(self, acfg, args, dev):
+        import torch
+        from paper_2402_01869_amd import binding as B
+        from paper_2402_01869_amd import workloads as W
+        self.acfg, self.dev = acfg, dev
+        H, D = acfg.num_heads, acfg.head_dim
+        self.pool_t = torch.empty(W.pool_shape(acfg.pool_blocks, acfg.kv_heads, 16, D), dtype=torch.bfloat16, device=dev)
+        W.fill_pool_device_normal(self.pool_t, acfg.seed, chunk_blocks=4096 if acfg.pool_blocks > (1 << 17) else 2048)
+        self.pool = B.KvPool.from_tensor(self.pool_t, H, D, num_kv_heads=acfg.kv_heads)
+        self.pool.set_tuning(args.decode_part, args.span_part, args.span_kernel, args.row_variant, args.serial_spans,
+                             args.row_launch, args.row_slots)
+        self.batches = [W.make_batch(acfg, acfg.seed), W.make_batch(acfg, acfg.seed + 1000)]
+        self.descs, self.qs, self.q_bits, self.outs = [], [], [], []
+        ws_bytes = 0
+        for i, b in enumerate(self.batches):
+            d = B.HostDesc.from_batch(b, flags=0)
+            q_bits = W.randn_bf16((b.total_q_rows, H, D), np.random.default_rng(acfg.seed + 7 + i))
+            self.descs.append(d)
+            self.q_bits.append(q_bits)
+            self.qs.append(torch.from_numpy(q_bits.view(np.int16)).to(dev))
+            self.outs.append(torch.zeros((b.total_q_rows, H, D), dtype=torch.int16, device=dev))
+            ws_bytes = max(ws_bytes, self.pool.workspace_bytes(d))
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.stream = torch.cuda.current_stream().cuda_stream
+        # one validated pass (full host checks), then trusted descriptors for the timed loops
+        for k in range(2):
+            self.call(k)
+        torch.cuda.synchronize()
+        for d in self.descs:
+            d.struct.flags = B.IC_FLAG_TRUSTED
+        self.kv_bytes = float(np.mean([b.kv_bytes() for b in self.batches]))
+        self.dec_bytes = float(np.mean([int(b.ctx_len[b.q_len == 1].astype(np.int64).sum()) * b.token_bytes
+                                        for b in self.batches]))
+        self.span_flops = float(np.mean([b.span_flops() for b in self.batches]))
+
+    def call(self, k, desc=None):
+        k &= 1
+        self.pool.paged_attn_mixed(desc or self.descs[k], self.qs[k].data_ptr(), self.outs[k].data_ptr(),
+                                   self.ws.data_ptr(), self.ws.numel(), self.stream)
+
+    def close(self):
+        self.pool.close()
+        del self.pool_t, self.ws, self.qs, self.outs
+
+
+def wall_ms(fn, n, warm):
+    """Wall time per call of fn(i), i = 0..n-1, after `warm` untimed calls; the GPU is drained on both sides."""
+    import torch
+    for i in range(warm):
+        fn(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n):
+        fn(i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / n
+
+
+def clock_ramp(fn, seconds):
+    """Run fn(i) back to back for `seconds` of wall time: after an idle gap the GPU's clocks take tens of milliseconds
+    to come up, and calls made meanwhile run up to 20 % slower.  Untimed, separate from the warm-up steps."""
+    import torch
+    t0, i = time.perf_counter(), 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(8):
+            fn(i)
+            i += 1
+        torch.cuda.synchronize()
+    return i
+
+
+def kernel_table(prof, steps=None):
+    out = {}
+    for k, v in prof.items():
+        if v["launches"]:
+            out[k] = {"launches": v["launches"], "avg_ms": round(v["total_ms"] / v["launches"], 5),
+                      "min_ms": round(v["min_ms"], 5), "max_ms": round(v["max_ms"], 5)}
+    return out
+
+
+def attention_kernel_names(pool, desc, acfg, args):
+    """Names of the kernels the default plan launches for this batch, from the planner's own report."""
+    info = pool.plan_query(desc)
+    D = acfg.head_dim
+    G = acfg.num_heads // acfg.kv_heads
+    grouped = 2 <= G <= 32 and G & (G - 1) == 0 and args.span_kernel == 0
+    beside = (info["tile_items"] > 0 and info["row_items"] > 0 and not args.serial_spans and D <= 128 and not grouped)
+    row = ("row_persist_slim_kernel" if beside or (args.row_launch == 3 and D <= 128) else
+           "row_attn_kernel" if args.row_launch == 1 else "row_persist_kernel")
+    return {"row": f"{row}<{D}>", "group": f"group_attn_kernel<{D}>",
+            "tile": f"{'tile_persist_kernel' if beside else 'tile_attn_kernel'}<{D}>", "merge": f"merge_kernel<{D}>",
+            "side_by_side": beside}
+
+
+def attention_report(S, args, steps, warm, default_plan):
+    """Times one attention workload: wall time per call, per-kernel HIP-event times, the call's roofline figures and the
+    dominant kernel's."""
+    acfg, pool = S.acfg, S.pool
+    names = attention_kernel_names(pool, S.descs[0], acfg, args)
+    ms = wall_ms(S.call, steps, warm)
+    pool.prof_begin(8 * steps + 8)
+    ms_ev = wall_ms(S.call, steps, 0)
+    prof = pool.prof_end()
+    kern = kernel_table({k: prof[k] for k in ("upload", "row", "group", "tile", "merge")})
+    roofline_ms = max(S.kv_bytes / (HBM_PEAK_GBPS * 1e9), S.span_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)) * 1e3
+    rep = {"workload": f"{acfg.name}: {acfg.n_decode} decode + {acfg.n_span}x{acfg.span_len}-row spans, H{acfg.num_heads}"
+                       f"{'/' + str(acfg.kv_heads) if acfg.kv_heads != acfg.num_heads else ''} D{acfg.head_dim}, "
+                       f"pool {acfg.pool_blocks} blocks",
+           "calls": steps, "ms": round(ms, 4), "ms_with_kernel_events": round(ms_ev, 4),
+           "kv_bytes": S.kv_bytes, "kv_read_GBps": round(S.kv_bytes / (ms * 1e-3) / 1e9, 1),
+           "frac_hbm_peak": round(S.kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+           "span_flops": S.span_flops, "roofline_time_ms": round(roofline_ms, 4),
+           "roofline_frac": round(roofline_ms / ms, 4),
+           "bound": "mfma" if S.span_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) > S.kv_bytes / (HBM_PEAK_GBPS * 1e9) else "hbm",
+           "side_by_side": names["side_by_side"],
+           "kernels": {names.get(k, k): v for k, v in kern.items()}}
+    tile_ms = kern.get("tile", {}).get("avg_ms")
+    if tile_ms:
+        rep["span_mfma_frac"] = round(S.span_flops / (tile_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
+    # dominant kernel: the longest of the call's kernels, priced against the roofline that bounds IT
+    cand = {k: kern[k]["avg_ms"] for k in ("row", "group", "tile") if k in kern}
+    dom = max(cand, key=cand.get)
+    rep["dominant_kernel"] = names[dom]
+    tkey = f"{acfg.name}/{dom}"
+    traffic = MEASURED_TRAFFIC.get(tkey) if default_plan else None
+    if dom == "tile":
+        ach = S.span_flops / (cand[dom] * 1e-3) / 1e12
+        roof = {"kernel": names[dom], "runs_beside": names["row"] if names["side_by_side"] else None, "bound": "mfma",
+                "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "flops_per_launch": S.span_flops}
+    else:
+        # its algorithmic bytes: the KV of the sequences it serves, each context once (everything if no tile kernel runs)
+        dom_bytes = S.kv_bytes if "tile" not in kern else S.dec_bytes
+        ach = dom_bytes / (cand[dom] * 1e-3) / 1e9
+        roof = {"kernel": names[dom], "runs_beside": names["tile"] if names["side_by_side"] else None, "bound": "hbm",
+                "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
+                "bytes_per_launch": dom_bytes}
+    roof["avg_launch_ms"] = cand[dom]
+    roof["traffic"] = traffic[0] if traffic else None
+    roof["traffic_source"] = (f"{traffic[1]} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command, "
+                              "calibrated on the pack kernel; not measured by this run)") if traffic else None
+    rep["roofline"] = roof
+    return rep, prof
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this hot path runs on ONE GPU (no sharding or collectives are built); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    from paper_2402_01869_amd import binding as B
+    B.lib()  # fail loudly if the HIP library is missing
     if args.mode != "hot_path":
-        sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
-        from paper_2402_01869_amd import binding as B
-        B.lib()
         return {"swap_pipeline": swap_pipeline_bench, "saturation": saturation_bench,
                 "ceilings": ceilings_bench}[args.mode](args)
     import torch
-    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
-    from paper_2402_01869_amd import binding as B
     from paper_2402_01869_amd import workloads as W
 
-    B.lib()  # fail loudly if the HIP library is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-
-    acfg = {"mixed_13b": W.MIXED_13B, "gptj_decode": W.GPTJ_DECODE, "long_ctx": W.LONG_CTX, "tiny": W.TINY,
-            "gqa_70b": W.GQA_70B}[args.workload]
+    acfg = W.ATTN_CONFIGS[args.workload]
     scfg = W.TINY_SWAP if args.workload == "tiny" else W.KV_SWAP
     if args.decode_only:
         import dataclasses
         acfg = dataclasses.replace(acfg, n_span=0)
     H, D = acfg.num_heads, acfg.head_dim
+    default_plan = not (args.decode_only or args.decode_part or args.span_part or args.serial_spans or args.span_kernel
+                        or args.row_launch or args.row_slots or args.row_variant)
 
-    # ---- attention inputs: one pool, two batches (different tables) alternated between steps
-    pool_t = torch.empty(W.pool_shape(acfg.pool_blocks, acfg.kv_heads, 16, D), dtype=torch.bfloat16, device=dev)
-    W.fill_pool_device_normal(pool_t, acfg.seed)
-    pool = B.KvPool.from_tensor(pool_t, H, D, num_kv_heads=acfg.kv_heads)
-    pool.set_tuning(args.decode_part, args.span_part, args.span_kernel, args.row_variant, args.serial_spans, args.row_launch, args.row_slots)
-    batches = [W.make_batch(acfg, acfg.seed), W.make_batch(acfg, acfg.seed + 1000)]
-    descs, qs, outs = [], [], []
-    ws_bytes = 0
-    for i, b in enumerate(batches):
-        d = B.HostDesc.from_batch(b, flags=0)
-        q_bits = W.randn_bf16((b.total_q_rows, H, D), np.random.default_rng(acfg.seed + 7 + i))
-        descs.append(d)
-        qs.append((torch.from_numpy(q_bits.view(np.int16)).to(dev), q_bits))
-        outs.append(torch.zeros((b.total_q_rows, H, D), dtype=torch.int16, device=dev))
-        ws_bytes = max(ws_bytes, pool.workspace_bytes(d))
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    S = AttnSetup(acfg, args, dev)
+    pool, stream = S.pool, S.stream
 
     # ---- swap inputs: its own pool (config shape), two staging buffers alternated
     do_swap = not args.no_swap
@@ -445,34 +583,25 @@ def main():
         src, dst = W.make_swap_lists(scfg)
         stagings = [torch.empty((scfg.n_move, scfg.block_bytes), dtype=torch.uint8, device=dev) for _ in range(2)]
         sbytes = stagings[0].numel()
-
-    stream = torch.cuda.current_stream().cuda_stream
-
-    # validated pass (full host checks), then trusted descriptors for the timed loop
-    for i in range(2):
-        pool.paged_attn_mixed(descs[i], qs[i][0].data_ptr(), outs[i].data_ptr(), ws.data_ptr(), ws.numel(), stream)
-        if do_swap:
-            spool.kv_pack_blocks(src, stagings[i].data_ptr(), sbytes, stream)
-    torch.cuda.synchronize()
-    for d in descs:
-        d.struct.flags = B.IC_FLAG_TRUSTED
+        for st_ in stagings:
+            spool.kv_pack_blocks(src, st_.data_ptr(), sbytes, stream)
 
     def step(i):
         k = i & 1
-        pool.paged_attn_mixed(descs[k], qs[k][0].data_ptr(), outs[k].data_ptr(), ws.data_ptr(), ws.numel(), stream)
+        S.call(k)
         if do_swap:
             spool.kv_pack_blocks(src, stagings[k].data_ptr(), sbytes, stream)
             spool.kv_unpack_blocks(dst, stagings[k ^ 1].data_ptr(), sbytes, stream)
 
     # Per-kernel HIP events are created now (and switched off again) so that nothing but a
-    # synchronize sits between the loops below: an idle gap lets the GPU clocks drop, and the first
-    # ~20 ms after it run up to 20 % slower.
+    # synchronize sits between the loops below.
     pool.prof_begin(8 * args.steps + 8)
     pool.prof_end()
     if do_swap:
         spool.prof_begin(4 * args.steps + 8)
         spool.prof_end()
 
+    ramp_steps = clock_ramp(step, args.clock_ramp)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -482,154 +611,113 @@ def main():
     for i in range(args.steps):
         step(i)
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # ---- loop 2: K more steps with a HIP event pair around every kernel, recorded by the library on
-    # the stream each kernel is launched on -> average launch durations for the roofline
+    # the stream each kernel is launched on -> average launch durations
     pool.prof_begin(8 * args.steps + 8)
     if do_swap:
         spool.prof_begin(4 * args.steps + 8)
-    tp = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    ms_per_step_events = (time.perf_counter() - tp) * 1e3 / args.steps
-    prof = pool.prof_end()
+    ms_per_step_events = wall_ms(step, args.steps, 0)
+    step_prof = pool.prof_end()
     if do_swap:
         sp = spool.prof_end()
-        prof["pack"], prof["unpack"] = sp["pack"], sp["unpack"]
+        step_prof["pack"], step_prof["unpack"] = sp["pack"], sp["unpack"]
 
-    # ---- loop 3: wall time of the attention call alone (kernels overlap inside it)
-    for i in range(min(10, args.steps)):
-        k = i & 1
-        pool.paged_attn_mixed(descs[k], qs[k][0].data_ptr(), outs[k].data_ptr(), ws.data_ptr(), ws.numel(), stream)
-    torch.cuda.synchronize()
-    ta = time.perf_counter()
-    for i in range(args.steps):
-        k = i & 1
-        pool.paged_attn_mixed(descs[k], qs[k][0].data_ptr(), outs[k].data_ptr(), ws.data_ptr(), ws.numel(), stream)
-    torch.cuda.synchronize()
-    attn_wall_ms = (time.perf_counter() - ta) * 1e3 / args.steps
+    # ---- loop 3: the attention call alone (kernels overlap inside it): wall time, per-kernel events, roofline
+    attn, _ = attention_report(S, args, args.steps, min(10, args.steps), default_plan)
 
     # ---- loop 3b: the same calls from descriptor images planned and uploaded once (what the layers after the
     # first do in an iteration: kernel launches only)
     plans, plan_ws = [], []
     for k in range(2):
-        w = torch.empty(pool.workspace_bytes(descs[k]), dtype=torch.uint8, device=dev)
+        w = torch.empty(pool.workspace_bytes(S.descs[k]), dtype=torch.uint8, device=dev)
         plan_ws.append(w)
-        plans.append(pool.plan_create(descs[k], w.data_ptr(), w.numel(), stream))
-    for timed in (False, True):
-        torch.cuda.synchronize()
-        tb = time.perf_counter()
-        for i in range(args.steps if timed else min(10, args.steps)):
-            k = i & 1
-            pool.paged_attn_planned(plans[k], qs[k][0].data_ptr(), outs[k].data_ptr(), stream)
-        torch.cuda.synchronize()
-    attn_planned_ms = (time.perf_counter() - tb) * 1e3 / args.steps
+        plans.append(pool.plan_create(S.descs[k], w.data_ptr(), w.numel(), stream))
+    attn_planned_ms = wall_ms(lambda i: pool.paged_attn_planned(plans[i & 1], S.qs[i & 1].data_ptr(),
+                                                                S.outs[i & 1].data_ptr(), stream),
+                              args.steps, min(10, args.steps))
     for pl in plans:
         pl.close()
 
     # ---- loop 4: the decode sequences alone and the recomputation spans alone (same tables, same q rows)
     def sub_call_ms(pick):
         subs = []
-        for b in batches:
+        for b in S.batches:
             sel = np.nonzero(pick(b))[0]
             if len(sel) == 0:
                 return None
             subs.append(B.HostDesc(b.ctx_len[sel], b.q_len[sel], b.q_start[sel], b.block_tables[sel], b.scale,
                                    total_q_rows=b.total_q_rows, flags=B.IC_FLAG_TRUSTED))
-            assert pool.workspace_bytes(subs[-1]) <= ws.numel()
+            assert pool.workspace_bytes(subs[-1]) <= S.ws.numel()
         n = max(10, args.steps // 2)
-        for timed in (False, True):
-            torch.cuda.synchronize()
-            t = time.perf_counter()
-            for i in range(n):
-                k = i & 1
-                pool.paged_attn_mixed(subs[k], qs[k][0].data_ptr(), outs[k].data_ptr(), ws.data_ptr(), ws.numel(), stream)
-            torch.cuda.synchronize()
-        return (time.perf_counter() - t) * 1e3 / n
+        return wall_ms(lambda i: S.call(i, subs[i & 1]), n, n)
 
     decode_alone_ms = sub_call_ms(lambda b: b.q_len == 1)
     spans_alone_ms = sub_call_ms(lambda b: b.q_len > 1)
 
-    # ---- loop 5 (outside the step): kv_write_span of the same batches, the step that precedes the
-    # attention call in an iteration; the rows written are random, the pool is refilled by nothing:
-    # attention outputs above were already taken.
+    # ---- loop 5: pack and unpack, each in loops of its own: SWAP_LOOP launches back to back inside ONE HIP event
+    # pair on the launch stream, two staging buffers alternating; several such loops, the median loop reported
+    swap = {}
+    swap_moved = 2.0 * scfg.n_move * scfg.block_bytes if do_swap else 0.0   # read + write, per call
+    if do_swap:
+        calls = {"pack": lambda i: spool.kv_pack_blocks(src, stagings[i & 1].data_ptr(), sbytes, stream),
+                 "unpack": lambda i: spool.kv_unpack_blocks(dst, stagings[i & 1].data_ptr(), sbytes, stream)}
+        for name, fn in calls.items():
+            for i in range(10):
+                fn(i)
+            per_launch = []
+            for rep in range(SWAP_REPS):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(SWAP_LOOP):
+                    fn(i)
+                e1.record()
+                e1.synchronize()
+                per_launch.append(e0.elapsed_time(e1) / SWAP_LOOP)
+            med = float(np.median(per_launch))
+            g = swap_moved / (med * 1e-3) / 1e9
+            kavg = step_prof[name]["total_ms"] / step_prof[name]["launches"]
+            swap[name] = {"moved_bytes": swap_moved, "GBps": round(g, 1), "frac_hbm_peak": round(g / HBM_PEAK_GBPS, 4),
+                          "ms_per_call_median": round(med, 5), "ms_per_call_min": round(min(per_launch), 5),
+                          "timing": f"median of {SWAP_REPS} loops of {SWAP_LOOP} back-to-back calls, one HIP event pair around "
+                                    "each loop on the launch stream; a call = id-list upload + the one gather / scatter launch",
+                          "kernel_avg_ms_in_step": round(kavg, 5),
+                          "kernel_GBps_in_step": round(swap_moved / (kavg * 1e-3) / 1e9, 1)}
+
+    # ---- loop 6 (outside the step): kv_write_span of the same batches, the step that precedes the attention call in
+    # an iteration; the rows written are random, the attention outputs above were already taken
     append = None
     if not args.no_append:
-        kn = [torch.randn((b.total_q_rows, acfg.kv_heads, D), device=dev).to(torch.bfloat16) for b in batches]
-        vn = [torch.randn((b.total_q_rows, acfg.kv_heads, D), device=dev).to(torch.bfloat16) for b in batches]
+        kn = [torch.randn((b.total_q_rows, acfg.kv_heads, D), device=dev).to(torch.bfloat16) for b in S.batches]
+        vn = [torch.randn((b.total_q_rows, acfg.kv_heads, D), device=dev).to(torch.bfloat16) for b in S.batches]
         n_ap = max(10, args.steps // 2)
         for timed in (False, True):
             if timed:
                 pool.prof_begin(2 * n_ap + 8)
             for i in range(n_ap):
                 k = i & 1
-                pool.kv_write_span(descs[k], kn[k].data_ptr(), vn[k].data_ptr(), stream)
+                pool.kv_write_span(S.descs[k], kn[k].data_ptr(), vn[k].data_ptr(), stream)
             torch.cuda.synchronize()
         ap = pool.prof_end()["append"]
         ap_ms = ap["total_ms"] / ap["launches"]
-        ap_bytes = float(np.mean([2.0 * 2 * b.total_q_rows * acfg.kv_heads * D * 2 for b in batches]))   # K and V, read + write
-        append = {"rows": int(np.mean([b.total_q_rows for b in batches])), "moved_bytes": ap_bytes,
+        ap_bytes = float(np.mean([2.0 * 2 * b.total_q_rows * acfg.kv_heads * D * 2 for b in S.batches]))   # K and V, read + write
+        append = {"rows": int(np.mean([b.total_q_rows for b in S.batches])), "moved_bytes": ap_bytes,
                   "avg_ms": round(ap_ms, 5), "min_ms": round(ap["min_ms"], 5),
                   "GBps": round(ap_bytes / (ap_ms * 1e-3) / 1e9, 1),
                   "frac_hbm_peak": round(ap_bytes / (ap_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        del kn, vn
 
-    kv_bytes = float(np.mean([b.kv_bytes() for b in batches]))
-    dec_bytes = float(np.mean([int(b.ctx_len[b.q_len == 1].astype(np.int64).sum()) * b.token_bytes for b in batches]))
-    span_flops = float(np.mean([b.span_flops() for b in batches]))
-    swap_moved = 2.0 * scfg.n_move * scfg.block_bytes if do_swap else 0.0   # read + write, per call
-    step_bytes = kv_bytes + 2 * swap_moved
-
-    # lower bound of the attention call: all KV bytes at HBM peak, or the spans' flops at MFMA peak
-    roofline_ms = max(kv_bytes / (HBM_PEAK_GBPS * 1e9), span_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)) * 1e3
-
-    def avg_ms(k):
-        return prof[k]["total_ms"] / prof[k]["launches"] if prof[k]["launches"] else None
-
-    plan = pool.plan_query(descs[0])
-    attn_ms = sum((avg_ms(k) or 0.0) * (prof[k]["launches"] / args.steps) for k in ("row", "tile", "merge"))
-    kernels = {}
-    for k in ("upload", "row", "tile", "merge", "pack", "unpack"):
-        if prof[k]["launches"]:
-            kernels[k] = {"launches": prof[k]["launches"], "avg_ms": round(avg_ms(k), 5),
-                          "min_ms": round(prof[k]["min_ms"], 5), "max_ms": round(prof[k]["max_ms"], 5)}
-
-    # Dominant kernel of the step: the row kernel (decode rows, HBM-bound).  In a mixed batch it runs
-    # beside the tile kernel, which reads the spans' keys at the same time; its own algorithmic bytes
-    # are the decode sequences' KV, each context once (all KV bytes if spans run row by row).
-    roofline = None
-    if prof["row"]["launches"]:
-        dom_bytes = kv_bytes if plan["tile_items"] == 0 else dec_bytes
-        ach = dom_bytes / (avg_ms("row") * 1e-3) / 1e9
-        G = H // acfg.kv_heads
-        grouped = 2 <= G <= 32 and G & (G - 1) == 0 and args.span_kernel == 0   # decode rows on the group kernel
-        beside = prof["tile"]["launches"] > 0 and not args.serial_spans and D <= 128 and not grouped
-        name = ("group_attn_kernel" if grouped else "row_persist_slim_kernel" if beside else
-                "row_attn_kernel" if args.row_launch == 1 else "row_persist_kernel")
-        roofline = {"kernel": name, "runs_beside": "tile_persist_kernel" if beside else None,
-                    "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
-                    "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
-                    "traffic": (MEASURED_TRAFFIC_BYTES.get(f"{args.workload}/row")
-                                if not (args.decode_only or args.decode_part or args.span_part or args.serial_spans)
-                                else None),
-                    "bytes_per_launch": dom_bytes, "avg_launch_ms": round(avg_ms("row"), 5)}
-
-    # Workloads whose floor is the spans' matrix work (long_ctx, gqa_70b): the dominant kernel is the tile kernel,
-    # priced against the dense bf16 MFMA peak.
-    if (prof["tile"]["launches"] and span_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) > kv_bytes / (HBM_PEAK_GBPS * 1e9)
-            and (not prof["row"]["launches"] or avg_ms("tile") > avg_ms("row"))):
-        G = H // acfg.kv_heads
-        grouped = 2 <= G <= 32 and G & (G - 1) == 0 and args.span_kernel == 0
-        persist = prof["row"]["launches"] > 0 and not args.serial_spans and D <= 128 and not grouped
-        ach = span_flops / (avg_ms("tile") * 1e-3) / 1e12
-        roofline = {"kernel": "tile_persist_kernel" if persist else "tile_attn_kernel",
-                    "runs_beside": "row_persist_slim_kernel" if persist else None,
-                    "bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS * 1.0,
-                    "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(f"{args.workload}/tile"),
-                    "flops_per_launch": span_flops, "avg_launch_ms": round(avg_ms("tile"), 5)}
+    step_bytes = S.kv_bytes + 2 * swap_moved
+    attn.update({"planned_ms": round(attn_planned_ms, 4),
+                 "planned_kv_read_GBps": round(S.kv_bytes / (attn_planned_ms * 1e-3) / 1e9, 1),
+                 "decode_kv_bytes": S.dec_bytes,
+                 "decode_alone_ms": None if decode_alone_ms is None else round(decode_alone_ms, 4),
+                 "decode_alone_GBps": (None if decode_alone_ms is None else
+                                       round(S.dec_bytes / (decode_alone_ms * 1e-3) / 1e9, 1)),
+                 "spans_alone_ms": None if spans_alone_ms is None else round(spans_alone_ms, 4),
+                 "plan": pool.plan_query(S.descs[0])})
+    roofline = attn.pop("roofline")
 
     result = {
         "metric": "mixed paged-attn KV-read GB/s (% HBM peak); swap pack/unpack GB/s",
@@ -638,6 +726,7 @@ def main():
         "value_definition": "algorithmic bytes of one step (KV bytes read once per sequence + pack read+write + "
                             "unpack read+write) / wall time of the step",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "clock_ramp_s": args.clock_ramp, "clock_ramp_steps": ramp_steps,
         "ms_per_step_with_kernel_events": round(ms_per_step_events, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
@@ -645,33 +734,40 @@ def main():
                                f"H{H} D{D}, pool {acfg.pool_blocks} blocks)"
                                + (f" + {scfg.name} ({scfg.n_move} of {scfg.pool_blocks} blocks x {scfg.block_bytes // 1024} KiB)" if do_swap else ""),
                    "decode_part_tokens": args.decode_part, "span_part_tokens": args.span_part, "span_kernel": args.span_kernel},
-        "attn": {"kv_bytes": kv_bytes, "ms": round(attn_wall_ms, 4), "sum_kernel_ms": round(attn_ms, 4),
-                 "kv_read_GBps": round(kv_bytes / (attn_wall_ms * 1e-3) / 1e9, 1),
-                 "frac_hbm_peak": round(kv_bytes / (attn_wall_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                 "planned_ms": round(attn_planned_ms, 4),
-                 "planned_kv_read_GBps": round(kv_bytes / (attn_planned_ms * 1e-3) / 1e9, 1),
-                 "decode_kv_bytes": dec_bytes,
-                 "decode_alone_ms": None if decode_alone_ms is None else round(decode_alone_ms, 4),
-                 "decode_alone_GBps": (None if decode_alone_ms is None else
-                                       round(dec_bytes / (decode_alone_ms * 1e-3) / 1e9, 1)),
-                 "spans_alone_ms": None if spans_alone_ms is None else round(spans_alone_ms, 4),
-                 "roofline_time_ms": round(roofline_ms, 4),
-                 "roofline_frac": round(roofline_ms / attn_wall_ms, 4),
-                 "span_flops": span_flops,
-                 "span_mfma_frac": (round(span_flops / (avg_ms("tile") * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
-                                    if prof["tile"]["launches"] else None),
-                 "plan": plan},
-        "kernels": kernels,
+        "attn": attn,
+        "step_kernels": kernel_table({k: step_prof[k] for k in ("upload", "row", "group", "tile", "merge", "pack", "unpack")}),
         "roofline": roofline,
     }
-    if do_swap:
-        for k in ("pack", "unpack"):
-            g = swap_moved / (avg_ms(k) * 1e-3) / 1e9
-            result[k] = {"moved_bytes": swap_moved, "GBps": round(g, 1), "frac_hbm_peak": round(g / HBM_PEAK_GBPS, 4)}
+    result.update(swap)
     if append:
         result["kv_write_span"] = append
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(batches[0], pool_t, qs[0][1], args.cpu_seconds)
+        result["cpu_baseline"] = cpu_baseline(S.batches[0], S.pool_t, S.q_bits[0], args.cpu_seconds)
+
+    # ---- the other attention configurations, one after the other (each with its own pool): driver-visible throughput
+    # of every config, a few dozen calls each
+    if args.workload == "mixed_13b" and default_plan and not args.no_other_configs:
+        if do_swap:
+            spool.close()
+            del spool_t, stagings
+        S.close()
+        del S
+        torch.cuda.empty_cache()
+        others = {}
+        n_other = max(10, min(args.steps, 30))
+        for name in ("gptj_decode", "gptj_mixed", "gqa_70b", "long_ctx"):
+            cfg = W.ATTN_CONFIGS[name]
+            free, _ = torch.cuda.mem_get_info()
+            if free < cfg.pool_blocks * cfg.block_bytes + (8 << 30):
+                others[name] = {"skipped": f"needs {cfg.pool_blocks * cfg.block_bytes >> 30} GiB of free HBM"}
+                continue
+            So = AttnSetup(cfg, args, dev)
+            clock_ramp(So.call, min(args.clock_ramp, 0.2))
+            others[name], _ = attention_report(So, args, n_other, min(10, n_other), True)
+            So.close()
+            del So
+            torch.cuda.empty_cache()
+        result["other_configs"] = others
     print(json.dumps(result))
 
 

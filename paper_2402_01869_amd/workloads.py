@@ -95,12 +95,16 @@ GQA_70B = AttnConfig("gqa_70b", 5, num_heads=64, head_dim=128, block_size=16, po
 LONG_CTX = AttnConfig("long_ctx", 4, num_heads=32, head_dim=128, block_size=16,
                       pool_blocks=524288, n_decode=256, decode_ctx=(1024, 8192),
                       n_span=16, span_len=2048, span_prefix=(16384, 16384))
+# GPT-J-6B-shaped mixed batch (Section 5's single-GPU model; Section 3.2: recomputation takes 37-40 % of its forwarding
+# time under the discard baseline): config 1's decode batch plus 8 recomputation chunks, head_dim 256
+GPTJ_MIXED = AttnConfig("gptj_mixed", 6, num_heads=16, head_dim=256, block_size=16, pool_blocks=16384,
+                        n_decode=64, decode_ctx=(512, 2048), n_span=8, span_len=512, span_prefix=(512, 2048))
 TINY_SWAP = SwapConfig("tiny_swap", 0, num_heads=4, head_dim=64, block_size=16,
                        pool_blocks=64, n_move=8)
 KV_SWAP = SwapConfig("kv_swap", 3, num_heads=40, head_dim=128, block_size=16,
                      pool_blocks=20000, n_move=2000)
 
-ATTN_CONFIGS: Dict[str, AttnConfig] = {c.name: c for c in (TINY, GPTJ_DECODE, MIXED_13B, LONG_CTX, GQA_70B)}
+ATTN_CONFIGS: Dict[str, AttnConfig] = {c.name: c for c in (TINY, GPTJ_DECODE, MIXED_13B, LONG_CTX, GQA_70B, GPTJ_MIXED)}
 SWAP_CONFIGS: Dict[str, SwapConfig] = {c.name: c for c in (TINY_SWAP, KV_SWAP)}
 
 
