@@ -489,8 +489,8 @@ def attention_kernel_names(pool, desc, acfg, args):
     beside = (info["tile_items"] > 0 and info["row_items"] > 0 and not args.serial_spans and D <= 128 and not grouped)
     row = ("row_persist_slim_kernel" if beside or (args.row_launch == 3 and D <= 128) else
            "row_attn_kernel" if args.row_launch == 1 else "row_persist_kernel")
-    return {"row": f"{row}<{D}>", "group": f"group_attn_kernel<{D}>",
-            "tile": f"{'tile_persist_kernel' if beside else 'tile_attn_kernel'}<{D}>", "merge": f"merge_kernel<{D}>",
+    tile = "tile_persist_kernel" if beside else "tile_attn_kernel"
+    return {"row": f"{row}<{D}>", "group": f"group_attn_kernel<{D}>", "tile": f"{tile}<{D}>", "merge": f"merge_kernel<{D}>",
             "side_by_side": beside}
 
 
@@ -661,27 +661,39 @@ def main():
     swap = {}
     swap_moved = 2.0 * scfg.n_move * scfg.block_bytes if do_swap else 0.0   # read + write, per call
     if do_swap:
-        calls = {"pack": lambda i: spool.kv_pack_blocks(src, stagings[i & 1].data_ptr(), sbytes, stream),
-                 "unpack": lambda i: spool.kv_unpack_blocks(dst, stagings[i & 1].data_ptr(), sbytes, stream)}
-        for name, fn in calls.items():
+        # a second pair of lists (the other way round), for loops in which no call finds its list already on the device
+        lists = {"pack": [src, dst], "unpack": [dst, src]}
+        calls = {"pack": lambda i, ids: spool.kv_pack_blocks(ids, stagings[i & 1].data_ptr(), sbytes, stream),
+                 "unpack": lambda i, ids: spool.kv_unpack_blocks(ids, stagings[i & 1].data_ptr(), sbytes, stream)}
+
+        def loop_ms(fn, pick):
             for i in range(10):
-                fn(i)
+                fn(i, pick(i))
             per_launch = []
             for rep in range(SWAP_REPS):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
                 for i in range(SWAP_LOOP):
-                    fn(i)
+                    fn(i, pick(i))
                 e1.record()
                 e1.synchronize()
                 per_launch.append(e0.elapsed_time(e1) / SWAP_LOOP)
-            med = float(np.median(per_launch))
+            return float(np.median(per_launch)), float(min(per_launch))
+
+        for name, fn in calls.items():
+            med, best = loop_ms(fn, lambda i: lists[name][0])                 # one list, call after call (a swap's layers)
+            med_new, _ = loop_ms(fn, lambda i: lists[name][i & 1])            # a new list every call
             g = swap_moved / (med * 1e-3) / 1e9
             kavg = step_prof[name]["total_ms"] / step_prof[name]["launches"]
             swap[name] = {"moved_bytes": swap_moved, "GBps": round(g, 1), "frac_hbm_peak": round(g / HBM_PEAK_GBPS, 4),
-                          "ms_per_call_median": round(med, 5), "ms_per_call_min": round(min(per_launch), 5),
+                          "ms_per_call_median": round(med, 5), "ms_per_call_min": round(best, 5),
                           "timing": f"median of {SWAP_REPS} loops of {SWAP_LOOP} back-to-back calls, one HIP event pair around "
-                                    "each loop on the launch stream; a call = id-list upload + the one gather / scatter launch",
+                                    "each loop on the launch stream; every call brings the same id list, as the layers of one "
+                                    "swap do, so the library uploads it once and a call is the one gather / scatter launch",
+                          "new_list_every_call": {"ms_per_call_median": round(med_new, 5),
+                                                  "GBps": round(swap_moved / (med_new * 1e-3) / 1e9, 1),
+                                                  "frac_hbm_peak": round(swap_moved / (med_new * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                                  "note": "a call = id-list upload + the launch"},
                           "kernel_avg_ms_in_step": round(kavg, 5),
                           "kernel_GBps_in_step": round(swap_moved / (kavg * 1e-3) / 1e9, 1)}
 

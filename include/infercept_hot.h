@@ -74,8 +74,10 @@ typedef struct ic_pool ic_pool; /* opaque; created by kv_pool_init, freed by kv_
  * block bytes (IC_ESIZE otherwise), 16-byte aligned.  Allocates no KV memory and touches no GPU
  * state.  The pool's own buffers are created by the first GPU call that needs them, sized from the
  * pool's shape so that later calls allocate nothing: four pinned host buffers for descriptors
- * (256 KiB + 8 bytes per block each) and one device id list (one int per cache slot: 64 bytes per
- * block).  A call that needs more (block tables that share blocks many times over, a pack list with
+ * (256 KiB + 8 bytes per block each) and three device int lists (block ids of a pack and of an
+ * unpack: one int per block each; row destinations of an append: one int per cache slot).  Each
+ * list remembers what it holds: a call whose list equals the previous one of its kind (the same
+ * blocks moved for every layer of a model) uploads nothing.  A call that needs more (block tables that share blocks many times over, a pack list with
  * many duplicates, more query rows than cache slots) allocates a larger buffer and keeps the old one
  * until kv_pool_destroy; no call waits for the device.
  */

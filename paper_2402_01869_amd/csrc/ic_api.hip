@@ -49,8 +49,16 @@ struct ic_pool {
   // library-owned runtime state (created lazily by the first GPU call)
   StagingSlot slots[kStagingSlots];
   int next_slot;
-  int32_t* dev_ids;
-  size_t dev_ids_cap;
+  // Device-side int32 lists, one per use (block ids of a pack, of an unpack, row destinations of an append), each
+  // with the host copy of what it holds: a call whose list equals the previous one's (the same blocks moved for
+  // every layer of a model, say) skips the upload and the checks that list already passed.
+  struct DevList {
+    int32_t* dev = nullptr;
+    size_t cap = 0;
+    std::vector<int32_t> held;  // contents of dev (from the last upload queued), empty = nothing usable
+    bool checked = false;       // ... which have passed the host checks (false: uploaded under IC_FLAG_TRUSTED)
+  };
+  DevList lists[3];
   std::vector<void*> retired_dev;   // id lists that were outgrown: earlier launches may still read them, freed at destroy
   std::vector<void*> retired_host;  // the same for pinned descriptor buffers
   int num_cus;           // compute units of the pool's device (0 until the first attention call)
@@ -385,12 +393,14 @@ hipStream_t shared_side_stream() {
 // Sizes of the pool's own buffers, fixed at the first GPU call from the pool's shape so that later calls
 // allocate nothing: a descriptor image is block tables (at most one entry per block while sequences
 // share none), work items and one int per query row; an id list is at most one entry per block (a
-// swap) or per cache slot (an append).  Only a call beyond these sizes grows a buffer, and then the
+// swap, one list each for packs and unpacks) or per cache slot (an append).  Only a call beyond these sizes grows a buffer, and then the
 // old one is kept until kv_pool_destroy (launches in flight may still read it) instead of being
 // freed behind a device-wide wait.
 size_t pinned_slot_bytes(const ic_pool* pool) { return align_up(((size_t)256 << 10) + 8 * (size_t)pool->cfg.num_blocks, 4096); }
-size_t dev_ids_bytes(const ic_pool* pool) {
-  return align_up(std::max((size_t)1 << 16, sizeof(int32_t) * (size_t)kBlockSize * (size_t)pool->cfg.num_blocks), 4096);
+enum { kListPack = 0, kListUnpack = 1, kListAppend = 2 };
+size_t dev_list_bytes(const ic_pool* pool, int which) {
+  const size_t entries = (size_t)pool->cfg.num_blocks * (which == kListAppend ? (size_t)kBlockSize : 1);
+  return align_up(std::max((size_t)1 << 16, sizeof(int32_t) * entries), 4096);
 }
 
 int acquire_slot(ic_pool* pool, size_t bytes, StagingSlot** out) {
@@ -482,8 +492,6 @@ int kv_pool_init(const ic_pool_cfg* cfg, void* dev_pool_base, size_t pool_bytes,
   p->block_bytes = bb;
   std::memset(&p->tune, 0, sizeof p->tune);
   p->next_slot = 0;
-  p->dev_ids = nullptr;
-  p->dev_ids_cap = 0;
   p->num_cus = 0;
   p->side = nullptr;
   p->ev_fork = p->ev_join = nullptr;
@@ -500,7 +508,8 @@ int kv_pool_destroy(ic_pool* pool) {
     if (s.host) (void)hipHostFree(s.host);
   }
   for (hipEvent_t e : pool->prof.ev) (void)hipEventDestroy(e);
-  if (pool->dev_ids) (void)hipFree(pool->dev_ids);
+  for (ic_pool::DevList& dl : pool->lists)
+    if (dl.dev) (void)hipFree(dl.dev);
   for (void* p : pool->retired_dev) (void)hipFree(p);
   for (void* p : pool->retired_host) (void)hipHostFree(p);
   if (pool->side && hipStreamSynchronize(pool->side) != hipSuccess) rc = IC_EHIP;  // shared: never destroyed
@@ -775,15 +784,49 @@ int paged_attn_plan_destroy(ic_plan* plan) {
 }
 
 // The pool's device-side int32 list (block ids of a swap, row destinations of an append).
-static int ensure_dev_ids(ic_pool* pool, size_t bytes) {
-  if (pool->dev_ids_cap >= bytes) return IC_OK;
-  const size_t cap = std::max(align_up(bytes, 4096), dev_ids_bytes(pool));
+static int ensure_dev_list(ic_pool* pool, int which, size_t bytes) {
+  ic_pool::DevList& dl = pool->lists[which];
+  if (dl.cap >= bytes) return IC_OK;
+  const size_t cap = std::max(align_up(bytes, 4096), dev_list_bytes(pool, which));
   int32_t* fresh = nullptr;
   if (hipMalloc((void**)&fresh, cap) != hipSuccess) return IC_EHIP;
-  if (pool->dev_ids) pool->retired_dev.push_back(pool->dev_ids);  // earlier launches may still read it
-  pool->dev_ids = fresh;
-  pool->dev_ids_cap = cap;
+  if (dl.dev) pool->retired_dev.push_back(dl.dev);  // earlier launches may still read it
+  dl.dev = fresh;
+  dl.cap = cap;
+  dl.held.clear();
   return IC_OK;
+}
+
+// Bring `n` ints into the pool's device list `which` on `st`, unless it holds exactly these already.
+static int upload_list(ic_pool* pool, int which, const int32_t* host, size_t n, bool checked, hipStream_t st) {
+  ic_pool::DevList& dl = pool->lists[which];
+  const size_t bytes = align_up(sizeof(int32_t) * n, 16);
+  int rc = ensure_dev_list(pool, which, bytes);
+  if (rc != IC_OK) return rc;
+  if (dl.held.size() == n && std::memcmp(dl.held.data(), host, sizeof(int32_t) * n) == 0) {
+    dl.checked = dl.checked || checked;
+    return IC_OK;
+  }
+  dl.held.clear();  // whatever fails below, the device copy is no longer known
+  dl.checked = checked;
+  StagingSlot* slot = nullptr;
+  if ((rc = acquire_slot(pool, bytes, &slot)) != IC_OK) return rc;
+  std::memcpy(slot->host, host, sizeof(int32_t) * n);
+  std::memset((char*)slot->host + sizeof(int32_t) * n, 0xff, bytes - sizeof(int32_t) * n);
+  {
+    ProfScope ps_(pool, IC_K_UPLOAD, st);
+    if (launch_upload(dl.dev, slot->host, bytes, st) != hipSuccess) return IC_EHIP;
+  }
+  if (hipEventRecord(slot->ev, st) != hipSuccess) return IC_EHIP;
+  slot->pending = true;
+  dl.held.assign(host, host + n);
+  return IC_OK;
+}
+
+// The device list holds exactly these ints and they have passed the host checks.
+static bool list_is_held(const ic_pool* pool, int which, const int32_t* host, size_t n) {
+  const ic_pool::DevList& dl = pool->lists[which];
+  return dl.checked && dl.held.size() == n && std::memcmp(dl.held.data(), host, sizeof(int32_t) * n) == 0;
 }
 
 static int swap_common(ic_pool* pool, const int32_t* host_ids, int32_t n, const void* dev_staging,
@@ -793,7 +836,9 @@ static int swap_common(ic_pool* pool, const int32_t* host_ids, int32_t n, const 
   if (n == 0) return IC_OK;
   if (!host_ids || !dev_staging) return IC_ENULL;
   return guarded([&]() -> int {
-  int rc = check_ids(pool->cfg, host_ids, n, !pack);
+  const int which = pack ? kListPack : kListUnpack;
+  // a list the device copy already holds has passed these checks
+  int rc = list_is_held(pool, which, host_ids, (size_t)n) ? IC_OK : check_ids(pool->cfg, host_ids, n, !pack);
   if (rc != IC_OK) return rc;
   if (misaligned(dev_staging)) return IC_EALIGN;
   if (staging_bytes / pool->block_bytes < (size_t)n) return IC_ESIZE;
@@ -803,24 +848,13 @@ static int swap_common(ic_pool* pool, const int32_t* host_ids, int32_t n, const 
     if (s0 < pool->base + pool->bytes && pool->base < s1) return IC_EINVAL;
   }
   hipStream_t st = (hipStream_t)hip_stream;
-  const size_t bytes = sizeof(int32_t) * (size_t)n;
-  if ((rc = ensure_dev_ids(pool, bytes)) != IC_OK) return rc;
-  StagingSlot* slot = nullptr;
-  const size_t padded = align_up(bytes, 16);
-  rc = acquire_slot(pool, padded, &slot);
-  if (rc != IC_OK) return rc;
-  std::memcpy(slot->host, host_ids, bytes);
-  {
-    ProfScope ps_(pool, IC_K_UPLOAD, st);
-    if (launch_upload(pool->dev_ids, slot->host, padded, st) != hipSuccess) return IC_EHIP;
-  }
-  if (hipEventRecord(slot->ev, st) != hipSuccess) return IC_EHIP;
-  slot->pending = true;
+  if ((rc = upload_list(pool, which, host_ids, (size_t)n, true, st)) != IC_OK) return rc;
+  const int32_t* dev_ids = pool->lists[which].dev;
   hipError_t e;
   {
     ProfScope ps_(pool, pack ? IC_K_PACK : IC_K_UNPACK, st);
-    e = pack ? launch_pack(pool->base, (void*)dev_staging, pool->dev_ids, n, pool->block_bytes, st)
-             : launch_unpack(pool->base, dev_staging, pool->dev_ids, n, pool->block_bytes, st);
+    e = pack ? launch_pack(pool->base, (void*)dev_staging, dev_ids, n, pool->block_bytes, st)
+             : launch_unpack(pool->base, dev_staging, dev_ids, n, pool->block_bytes, st);
   }
   return e == hipSuccess ? IC_OK : IC_EHIP;
   });
@@ -845,26 +879,17 @@ int kv_write_span(ic_pool* pool, const ic_batch_desc* desc, const void* dev_k_ne
   if (rc != IC_OK) return rc;
   if (misaligned(dev_k_new) || misaligned(dev_v_new)) return IC_EALIGN;
   const size_t rows = (size_t)desc->total_q_rows;
-  const size_t bytes = align_up(sizeof(int32_t) * rows, 16);
-  std::vector<int32_t> dst(bytes / sizeof(int32_t), -1);
+  std::vector<int32_t> dst(rows, -1);
   append_destinations(desc, dst.data());
-  if (!trusted && !destinations_distinct(pool->cfg, dst.data(), rows)) return IC_EDUP;
-  if ((rc = ensure_dev_ids(pool, bytes)) != IC_OK) return rc;
-  StagingSlot* slot = nullptr;
-  if ((rc = acquire_slot(pool, bytes, &slot)) != IC_OK) return rc;
-  std::memcpy(slot->host, dst.data(), bytes);
+  if (!trusted && !list_is_held(pool, kListAppend, dst.data(), rows) && !destinations_distinct(pool->cfg, dst.data(), rows))
+    return IC_EDUP;
   hipStream_t st = (hipStream_t)hip_stream;
-  {
-    ProfScope ps_(pool, IC_K_UPLOAD, st);
-    if (launch_upload(pool->dev_ids, slot->host, bytes, st) != hipSuccess) return IC_EHIP;
-  }
-  if (hipEventRecord(slot->ev, st) != hipSuccess) return IC_EHIP;
-  slot->pending = true;
+  if ((rc = upload_list(pool, kListAppend, dst.data(), rows, !trusted, st)) != IC_OK) return rc;
   hipError_t e;
   {
     ProfScope ps_(pool, IC_K_APPEND, st);
-    e = launch_append(pool->base, dev_k_new, dev_v_new, pool->dev_ids, desc->total_q_rows, pool->cfg.num_kv_heads,
-                      pool->cfg.head_dim, st);
+    e = launch_append(pool->base, dev_k_new, dev_v_new, pool->lists[kListAppend].dev, desc->total_q_rows,
+                      pool->cfg.num_kv_heads, pool->cfg.head_dim, st);
   }
   return e == hipSuccess ? IC_OK : IC_EHIP;
   });

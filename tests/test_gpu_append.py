@@ -157,3 +157,33 @@ def test_mixed_13b_shape_append_sampled():
     assert np.array_equal(from_dev_bits(view[idx]), small)
     assert view[mask].to(torch.int64).sum().item() == rest_before, "blocks outside the batch's new positions changed"
     pool.close()
+
+
+def test_repeated_batches_and_the_trusted_flag():
+    """kv_write_span keeps the device copy of the rows' destinations and skips the upload when the next call's batch
+    has the same ones (every layer of an iteration).  Same batch with new K/V rows, another batch, the first again:
+    always the oracle's bytes.  A destination list uploaded under IC_FLAG_TRUSTED has not been checked: the same
+    list without the flag is still checked (two rows on one slot are refused)."""
+    H, D = 3, 64
+    rng = np.random.default_rng(5)
+    b1 = W.assemble_batch(H, D, 16, 64, [40, 17, 100, 5], [1, 17, 30, 1], rng)
+    b2 = W.assemble_batch(H, D, 16, 64, [33, 64, 90, 9], [1, 20, 27, 1], rng)
+    assert b1.total_q_rows == b2.total_q_rows
+    pool_bits = W.randn_bf16(W.pool_shape(64, H, 16, D), rng)
+    want = pool_bits.copy()
+    pool, pool_t = make_pool(pool_bits)
+    for step, b in enumerate([b1, b1, b2, b1, b2, b2]):
+        k_new, v_new = W.randn_bf16((b.total_q_rows, H, D), rng), W.randn_bf16((b.total_q_rows, H, D), rng)
+        oracle.kv_append(want, b.ctx_len, b.q_len, b.q_start, b.block_tables, k_new, v_new)
+        k_t, v_t = to_dev_bits(k_new), to_dev_bits(v_new)
+        pool.kv_write_span(B.HostDesc.from_batch(b), k_t.data_ptr(), v_t.data_ptr())
+        torch.cuda.synchronize()
+        assert np.array_equal(from_dev_bits(pool_t), want), step
+    # two decode sequences whose new tokens land on one slot
+    dup = W.assemble_batch(H, D, 16, 64, [40, 40, 9], [1, 1, 1], rng)
+    dup.block_tables[1] = dup.block_tables[0]
+    k_t = to_dev_bits(W.randn_bf16((3, H, D), rng))
+    assert pool.kv_write_span(B.HostDesc.from_batch(dup, flags=B.IC_FLAG_TRUSTED), k_t.data_ptr(), k_t.data_ptr(), check=False) == B.IC_OK
+    torch.cuda.synchronize()
+    assert pool.kv_write_span(B.HostDesc.from_batch(dup), k_t.data_ptr(), k_t.data_ptr(), check=False) == B.IC_EDUP
+    pool.close()

@@ -135,3 +135,42 @@ def test_paged_read_ceiling_runs_on_every_head_dim(D):
     assert 1.0 < g < 8800.0, g
     assert torch.equal(pool_t, before)
     pool.close()
+
+
+def test_repeated_and_changing_id_lists():
+    """The library keeps the device copy of the last pack list and of the last unpack list and skips the upload
+    when a call brings the same list again (one swap = the same blocks for every layer).  Same list with changed
+    pool contents, another list of the same length, a shorter list, the first list again: always the oracle's bytes."""
+    H, D, blocks, n = 2, 64, 300, 40
+    bb = 16 * 2 * H * D * 2
+    rng = np.random.default_rng(31)
+    host = rng.integers(0, 256, size=(blocks, bb), dtype=np.uint8)
+    pool_t = torch.from_numpy(host.copy()).to(DEV)
+    pool = B.KvPool(B.make_cfg(blocks, H, D), pool_t.data_ptr(), pool_t.numel())
+    staging = torch.zeros((n, bb), dtype=torch.uint8, device=DEV)
+    a = rng.permutation(blocks)[:n].astype(np.int32)
+    b = rng.permutation(blocks)[:n].astype(np.int32)
+    for step, ids in enumerate([a, a, b, a[:7], a, b, b]):
+        if step % 2:      # change what the listed blocks hold between calls with the same list
+            host[ids[0]] = rng.integers(0, 256, size=bb, dtype=np.uint8)
+            pool_t[int(ids[0])] = torch.from_numpy(host[ids[0]]).to(DEV)
+        staging.fill_(0x11)
+        pool.kv_pack_blocks(ids, staging.data_ptr(), staging.numel())
+        torch.cuda.synchronize()
+        got = staging.cpu().numpy()
+        assert np.array_equal(got[:len(ids)], oracle.pack_blocks(host, ids)), step
+        assert (got[len(ids):] == 0x11).all(), step
+    # unpack: the same destinations twice with different staging contents, then other destinations
+    for step, ids in enumerate([a, a, b, b[:5], a]):
+        src = rng.integers(0, 256, size=(n, bb), dtype=np.uint8)
+        staging.copy_(torch.from_numpy(src).to(DEV))
+        pool.kv_unpack_blocks(ids, staging.data_ptr(), staging.numel())
+        torch.cuda.synchronize()
+        oracle.unpack_blocks(host, ids, src[:len(ids)])
+        assert np.array_equal(pool_t.cpu().numpy(), host), step
+    # a list with a duplicate destination is refused also right after a call with the same length
+    dup = a.copy(); dup[3] = dup[9]
+    assert pool.kv_unpack_blocks(dup, staging.data_ptr(), staging.numel(), check=False) == B.IC_EDUP
+    pool.kv_unpack_blocks(a, staging.data_ptr(), staging.numel())
+    torch.cuda.synchronize()
+    pool.close()
