@@ -21,15 +21,14 @@ import numpy as np
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
 # command, scaled by the pack kernel's known 640 000 KiB (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 on this GPU);
-# figures and commands in profiles/row_and_tile_persist_kernels_mixed_13b.md,
-# profiles/row_persist_kernel_gptj_decode.md, profiles/group_and_tile_kernels_gqa_70b.md and
-# profiles/tile_persist_kernel_long_ctx.md.  Only valid for the
-# default launch plan of these workloads.
-MEASURED_TRAFFIC = {"mixed_13b/row": ((2837644 * 2.0 + 4263) * 1024, "profiles/row_and_tile_persist_kernels_mixed_13b.md"),
-                    "gptj_decode/row": ((660656 * 2.0 + 3278) * 1024, "profiles/row_persist_kernel_gptj_decode.md"),
-                    "gqa_70b/group": ((537675 * 2.0 + 5144) * 1024, "profiles/group_and_tile_kernels_gqa_70b.md"),
-                    "gqa_70b/tile": ((84887 * 2.0 + 65536) * 1024, "profiles/group_and_tile_kernels_gqa_70b.md"),
-                    "long_ctx/tile": ((6133628 * 2.0 + 262292) * 1024, "profiles/tile_persist_kernel_long_ctx.md")}
+# figures and commands in the profiles/ file named next to each.  Only valid for the default launch plan of
+# these workloads; the JSON line says where the figure comes from (`traffic_source`).
+MEASURED_TRAFFIC = {"mixed_13b/row": ((2837974 * 2.0 + 4272) * 1024, "profiles/row_and_tile_persist_kernels_mixed_13b.md"),
+                    "gptj_decode/row": ((660607 * 2.0 + 3287) * 1024, "profiles/row_persist_kernel_gptj_decode.md"),
+                    "gptj_mixed/tile": ((129954 * 2.0 + 32768) * 1024, "profiles/tile_and_row_kernels_gptj_mixed.md"),
+                    "gqa_70b/group": ((537278 * 2.0 + 5139) * 1024, "profiles/group_and_tile_kernels_gqa_70b.md"),
+                    "gqa_70b/tile": ((84913 * 2.0 + 65536) * 1024, "profiles/group_and_tile_kernels_gqa_70b.md"),
+                    "long_ctx/tile": ((6120629 * 2.0 + 262291) * 1024, "profiles/tile_persist_kernel_long_ctx.md")}
 SWAP_LOOP, SWAP_REPS = 50, 7   # pack / unpack timing: launches per event pair, loops
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, vendor figure
 
