@@ -676,7 +676,7 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
     const bool joined = hipEventRecord(pool->ev_join, pool->side) == hipSuccess;
     if (ok) {
       ProfScope ps_(pool, IC_K_ROW, st);
-      ok = launch_row_persist_slim(p, D, pool->num_cus, st) == hipSuccess;
+      ok = launch_row_persist_slim(p, D, pool->tune.row_slots > 0 ? pool->tune.row_slots : pool->num_cus, st) == hipSuccess;
     }
     if (!joined || hipStreamWaitEvent(st, pool->ev_join, 0) != hipSuccess) {
       (void)hipStreamSynchronize(pool->side);
