@@ -413,10 +413,47 @@ def test_mixed_13b_config_full():
     pool.close()
 
 
-def test_gqa_70b_config_sampled():
+def test_gptj_mixed_config_full():
+    """GPT-J-6B-shaped mixed batch (head_dim 256: the decode batch of config 1 plus 8 recomputation spans of 512 rows)
+    at full size, in the launch configuration the benchmark times (128-row tiles, then the row kernel): every element
+    of every row."""
+    cfg = W.GPTJ_MIXED
+    batch = W.make_batch(cfg)
+    pool_t = torch.empty(W.pool_shape(cfg.pool_blocks, cfg.num_heads, 16, cfg.head_dim), dtype=torch.bfloat16, device=DEV)
+    W.fill_pool_device_normal(pool_t, cfg.seed)
+    q_bits = W.randn_bf16((batch.total_q_rows, cfg.num_heads, cfg.head_dim), np.random.default_rng(cfg.seed))
+    pool = B.KvPool.from_tensor(pool_t, cfg.num_heads, cfg.head_dim)
+    r = AttnRunner(pool, batch, q_bits, flags=B.IC_FLAG_TRUSTED)
+    info = pool.plan_query(r.desc)
+    assert info["tile_items"] == 8 * 4 and info["span_rows"] == 8 * 512
+    out = r.run()
+    assert np.isfinite(W.bf16_bits_to_f64(out)).all()
+
+    def fetch(ids):
+        return from_dev_bits(pool_t.view(torch.int16)[torch.from_numpy(ids).to(DEV)])
+
+    rec = Recorded()
+    for s0 in range(0, batch.num_seqs, 8):
+        seqs = list(range(s0, min(batch.num_seqs, s0 + 8)))
+        small, sub = W.compact_referenced(batch, seqs, fetch)
+        iseq, irow = [], []
+        for j, s in enumerate(seqs):
+            rows = list(range(int(batch.q_len[s])))
+            iseq += [j] * len(rows); irow += rows
+        want = oracle.paged_attn_items(small, sub.ctx_len, sub.q_len, sub.q_start, sub.block_tables, q_bits,
+                                       sub.scale, iseq, irow)
+        grow = [int(sub.q_start[j]) + i for j, i in zip(iseq, irow)]
+        rec.add(W.bf16_bits_to_f64(out[grow]), want)
+    rec.report("gptj_mixed")
+    assert rec.worst <= TOL, rec.worst
+    pool.close()
+
+
+@pytest.mark.timeout(600)
+def test_gqa_70b_config_full():
     """70B-shaped grouped-query batch (64 query heads over 8 K/V heads) at full size, in the launch configuration the
-    benchmark times (group kernel for the decode rows, head-group tiles for the chunks): every decode row and a
-    deterministic sample of span rows, all 64 heads of each."""
+    benchmark times (group kernel for the decode rows, head-group tiles for the chunks): every element of every row,
+    all 64 heads of each."""
     cfg = W.GQA_70B
     batch = W.make_batch(cfg)
     Hkv = cfg.num_kv_heads
@@ -431,19 +468,19 @@ def test_gqa_70b_config_sampled():
     def fetch(ids):
         return from_dev_bits(pool_t.view(torch.int16)[torch.from_numpy(ids).to(DEV)])
 
-    span_rows = [0, 1, 3, 4, 15, 16, 17, 31, 32, 33, 127, 128, 255, 256, 300, 511]   # 4-row head-group tile edges too
     rec = Recorded()
     for s0 in range(0, batch.num_seqs, 8):
         seqs = list(range(s0, min(batch.num_seqs, s0 + 8)))
         small, sub = W.compact_referenced(batch, seqs, fetch)
         iseq, irow = [], []
         for j, s in enumerate(seqs):
-            rows = [0] if batch.q_len[s] == 1 else span_rows
+            rows = list(range(int(batch.q_len[s])))
             iseq += [j] * len(rows); irow += rows
         want = oracle.paged_attn_items(small, sub.ctx_len, sub.q_len, sub.q_start, sub.block_tables, q_bits,
                                        sub.scale, iseq, irow)
         grow = [int(sub.q_start[j]) + i for j, i in zip(iseq, irow)]
         rec.add(W.bf16_bits_to_f64(out[grow]), want)
+        print(f"gqa_70b: sequences {s0}..{seqs[-1]} checked", flush=True)
     rec.report("gqa_70b")
     assert rec.worst <= TOL, rec.worst
     pool.close()
