@@ -188,6 +188,27 @@ def test_random_batches_with_outputs_of_magnitude_two_and_more(seed):
     _check_batch(batch, 9100 + seed, tunings=tunings, grid_slack=True)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_long_batches_and_plans(seed):
+    """The same idea at longer shapes: contexts to 9000 tokens (several key partitions per decode row), chunks to 600
+    rows (three query tiles), head groups to 32, default plan and one random plan each; flat bar."""
+    rng = np.random.default_rng(52000 + seed)
+    D = int(rng.choice([64, 128, 128, 256]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 1, 2, 8, 16, 32, 5])) if D < 256 else int(rng.choice([1, 2, 4]))
+    ctx, qlen = [], []
+    for _ in range(int(rng.integers(2, 7))):
+        c = int(rng.integers(16, 9000))
+        q = 1 if rng.integers(0, 3) == 0 else int(rng.integers(2, min(c, 600) + 1))
+        ctx.append(c); qlen.append(q)
+    blocks = sum(-(-c // 16) for c in ctx) + 3
+    batch = W.assemble_batch(Hkv * G, D, 16, blocks, ctx, qlen, rng, num_kv_heads=Hkv)
+    part = lambda: int(rng.choice([0, 0, 256, 1024, 4096]))
+    tunings = [dict(), dict(decode_part_tokens=part(), span_part_tokens=part(), span_kernel=int(rng.integers(0, 3)),
+                            serial_spans=int(rng.integers(0, 2)), row_launch=int(rng.integers(0, 4)))]
+    _check_batch(batch, 52100 + seed, tunings=tunings)
+
+
 @pytest.mark.parametrize("H,Hkv,D,tuning", [(5, 5, 128, dict()), (5, 5, 128, dict(serial_spans=1, decode_part_tokens=128)),
                                             (4, 4, 256, dict()), (16, 2, 128, dict()), (3, 3, 64, dict(span_kernel=1)),
                                             (8, 8, 64, dict(span_part_tokens=128, decode_part_tokens=64))])
