@@ -373,6 +373,16 @@ void plan_fill(const ic_batch_desc* d, const PlanSizes& ps, char* img) {
         }
     }
   }
+  // Longest tile items first: workgroups are handed out in item order (per head), and a few hundred items of
+  // unequal length (contexts differ 3 : 1) over 256 CUs otherwise end with the longest ones running alone.  The
+  // query tiles of one sequence differ by one tile height in length, so they stay next to each other.
+  std::stable_sort(tiles, tiles + ntiles, [](const TileItem& a, const TileItem& b) {
+    return (int64_t)(a.k_end - a.k_begin) * a.n_rows > (int64_t)(b.k_end - b.k_begin) * b.n_rows;
+  });
+  // The same for row items, within the vector kernel's and the group kernel's share: decode contexts differ 16 : 1.
+  const auto longer = [](const RowItem& a, const RowItem& b) { return a.k_end - a.k_begin > b.k_end - b.k_begin; };
+  std::stable_sort(rows, rows + ps.vec_items, longer);
+  std::stable_sort(rows + ps.vec_items, rows + ps.info.row_items, longer);
 }
 
 // ---------------------------------------------------------------------------------------
