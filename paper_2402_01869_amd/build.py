@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libinfercept_hot.so")
-SOURCES = ["ic_api.hip", "kv_swap.hip", "swap_pipe.hip", "waste_model.hip", "attn_row.hip", "attn_tile.hip", "attn_group.hip",
+SOURCES = ["ic_api.hip", "kv_swap.hip", "swap_pipe.hip", "waste_model.hip", "attn_row.hip", "attn_tile.hip", "attn_group.hip", "attn_group_slim.hip",
            "ceilings.hip"]
 HEADERS = [os.path.join(CSRC, "ic_internal.h"), os.path.join(CSRC, "row_body.h"), os.path.join(CSRC, "tile_body.h"),
            os.path.join(os.path.dirname(HERE), "include", "infercept_hot.h"),

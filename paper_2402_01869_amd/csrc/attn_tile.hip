@@ -31,6 +31,7 @@ template <int D>
 __global__ __launch_bounds__(TW<D>::kThreads, (D <= 128 ? 2 : 1)) void tile_persist_kernel(AttnParams p) {
   __shared__ __attribute__((aligned(16))) uint16_t lds[tile_lds_bytes<D>() / 2];
   __shared__ int s_next;
+  if (p.tile_first) __builtin_amdgcn_s_setprio(3);
   const int H = p.num_heads >> p.tile_g_shift;               // head groups
   const bool per_xcd = H >= 8;   // with fewer head groups than XCDs, one shared queue instead
   const uint32_t x = blockIdx.x & 7u;

@@ -179,6 +179,7 @@ struct PlanSizes {
   bool spans_as_rows;
   bool decode_as_tiles;                // grouped pools, span_kernel = 2: decode rows as one-row tile items
   bool decode_as_group;                // grouped pools: decode rows stay row items, run by the group kernel
+  bool tile_leads;                     // the tile items are expected to take longer than the row items
   size_t off_ctr, off_bt_off, off_bt_flat, off_row, off_tile, off_merge, off_row_dst, image_bytes;
   size_t off_part_o, off_part_ml, total_bytes;
 };
@@ -250,6 +251,7 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
     if (tiles * head_groups >= kUnsplitWorkgroups) ps.span_part = 1 << 30;
   }
   ic_plan_info& in = ps.info;
+  double tile_pairs = 0, row_keys = 0;  // (query row, key) pairs of the tile items; keys of the row items
   for (int s = 0; s < d->num_seqs; ++s) {
     const int c = d->ctx_len[s], n = d->q_len[s];
     in.table_entries += (c + kBlockSize - 1) / kBlockSize;
@@ -260,6 +262,7 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
       const int klen = c - n + i + 1;
       const int parts = (klen + ps.row_part - 1) / ps.row_part;
       in.row_items += parts;
+      row_keys += klen;
       if (i < rt.n_few || !rt.rest_group) ps.vec_items += parts;
       if (parts > 1) { in.partial_slots += parts; in.merge_rows += 1; }
     }
@@ -270,11 +273,16 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
         const int klen = c - n + r0 + nr;  // keys visible to the tile's last row
         const int parts = (klen + part - 1) / part;
         in.tile_items += parts;
+        tile_pairs += (double)nr * (klen - 0.5 * nr);
         if (parts > 1) { in.partial_slots += parts * nr; in.merge_rows += nr; }
       }
     }
   }
   const int H = pool->cfg.num_heads, D = pool->cfg.head_dim;
+  // Which of the two kernels of a side-by-side launch ends last, from the rates they reach there (tile kernel
+  // 0.9 PFLOP/s at 4 D flop per pair and head, row kernels 5.5 TB/s at 4 D bytes per key and K/V head): that one
+  // goes on the caller's stream, the other through the fork and join of the second stream.
+  ps.tile_leads = tile_pairs * H * (4.0 * D / 0.9e15) > row_keys * pool->cfg.num_kv_heads * (4.0 * D / 5.5e12);
   size_t o = 0;
   ps.off_ctr = o;     o = align_up(o + sizeof(int32_t) * 16, 256);
   ps.off_bt_off = o;  o = align_up(o + sizeof(int32_t) * (size_t)d->num_seqs, 256);
@@ -663,18 +671,22 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
   p.n_merge_items = ps.info.merge_rows;
   p.scale_log2e = scale * 1.4426950408889634f;
   p.row_variant = pool->tune.row_variant;
+  p.tile_first = 0;
   p.counters = (int32_t*)(ws + ps.off_ctr);
 
   // Decode rows are memory-bound and span tiles are MFMA-bound (the complementarity Section 4.2
   // builds on): a batch that has both runs them as two persistent kernels side by side, one
   // workgroup of each per CU, the tile kernel on the pool's second stream (forked from and joined
-  // back into the caller's stream by events).  serial_spans = 1, and head_dim 256 (whose tile
-  // workgroup leaves no registers for a neighbour), run one kernel after the other instead.
-  // Grouped pools run the tile kernel, then the group kernel (measured: as two ordinary launches on
-  // two streams they overlap by 2 %, not worth a second queue).
-  const bool beside = p.n_tile_items > 0 && p.n_vec_items > 0 && !pool->tune.serial_spans && D <= 128 &&
-                      !ps.decode_as_group;
-  if (beside) {
+  // back into the caller's stream by events).  The kernel beside the tile kernel is the slim row
+  // kernel (multi-head pools) or the slim group kernel (grouped pools: head_dim 128, groups of up
+  // to 16 heads).  serial_spans = 1, head_dim 256 (whose tile workgroup leaves no registers for a
+  // neighbour) and the other grouped shapes run one kernel after the other instead.
+  const int n_group_items = p.n_row_items - p.n_vec_items;
+  const bool pair_ok = p.n_tile_items > 0 && !pool->tune.serial_spans && D <= 128;
+  const bool beside_rows = pair_ok && p.n_vec_items > 0 && !ps.decode_as_group;
+  const bool beside_group = pair_ok && n_group_items > 0 && D == 128 && p.group <= 16;
+  const int row_slots = pool->tune.row_slots > 0 ? pool->tune.row_slots : pool->num_cus;
+  if (beside_rows || beside_group) {
     if (!pool->side) {  // the stream is assigned last: a half-made set is retried by the next call
       if (!pool->ev_fork && hipEventCreateWithFlags(&pool->ev_fork, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
       if (!pool->ev_join && hipEventCreateWithFlags(&pool->ev_join, hipEventDisableTiming) != hipSuccess) return IC_EHIP;
@@ -684,15 +696,38 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
     if (hipStreamWaitEvent(pool->side, pool->ev_fork, 0) != hipSuccess) return IC_EHIP;
     // From here on the side stream may hold work that writes dev_out and the workspace: whatever fails
     // below, the caller's stream is still made to wait for it (or, failing that, the host does).
+    // The kernel expected to end last runs on the caller's stream, where nothing but the upload is in front of it;
+    // the other one pays the two cross-stream waits (some 10 us each).  A tile kernel that leads also asks for
+    // issue priority: what it loses to its neighbour's waves is lost to the call (measured on the 70B-shaped
+    // batch: tile kernel 0.455 instead of 0.492 ms, group kernel 0.24 instead of 0.21 ms, call 0.50 instead of 0.53).
+    const bool tile_main = ps.tile_leads;
+    hipStream_t s_tile = tile_main ? st : pool->side, s_rows = tile_main ? pool->side : st;
+    p.tile_first = tile_main;
     bool ok = true;
-    {
-      ProfScope ps_(pool, IC_K_TILE, pool->side);
-      ok = launch_tile_persist(p, D, pool->num_cus, pool->side) == hipSuccess;
-    }
-    const bool joined = hipEventRecord(pool->ev_join, pool->side) == hipSuccess;
-    if (ok) {
-      ProfScope ps_(pool, IC_K_ROW, st);
-      ok = launch_row_persist_slim(p, D, pool->tune.row_slots > 0 ? pool->tune.row_slots : pool->num_cus, st) == hipSuccess;
+    auto run_tile = [&] {
+      ProfScope ps_(pool, IC_K_TILE, s_tile);
+      ok = launch_tile_persist(p, D, pool->num_cus, s_tile) == hipSuccess;
+    };
+    auto run_rows = [&] {
+      if (ok && beside_group) {
+        ProfScope ps_(pool, IC_K_GROUP, s_rows);
+        ok = launch_group_slim(p, D, row_slots, s_rows) == hipSuccess;
+      }
+      if (ok && p.n_vec_items > 0) {  // in a grouped pool: the rows with too few keys for the matrix cores
+        ProfScope ps_(pool, IC_K_ROW, s_rows);
+        ok = launch_row_persist_slim(p, D, row_slots, s_rows) == hipSuccess;
+      }
+    };
+    // the tile workgroups are placed first either way: one per CU, the row workgroups fill in beside them
+    bool joined;
+    if (tile_main) {
+      run_tile();
+      run_rows();
+      joined = hipEventRecord(pool->ev_join, pool->side) == hipSuccess;
+    } else {
+      run_tile();
+      joined = hipEventRecord(pool->ev_join, pool->side) == hipSuccess;
+      run_rows();
     }
     if (!joined || hipStreamWaitEvent(st, pool->ev_join, 0) != hipSuccess) {
       (void)hipStreamSynchronize(pool->side);
@@ -702,21 +737,20 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
   } else {
     if (p.n_tile_items > 0) {
       ProfScope ps_(pool, IC_K_TILE, st);
-      // head_dim <= 128: the persistent launch also when no row kernel runs beside it.  Its per-XCD queues keep the
+      // head_dim <= 128: the persistent launch also when no other kernel runs beside it.  Its per-XCD queues keep the
       // query tiles of one (sequence, head) on one L2: on 2048-row chunks the spans then fetch 2.6 x instead of 6.9 x
       // their keys from HBM and finish 7 % sooner (9.66 against 10.41 ms); shorter chunks and grouped pools: no change.
       const hipError_t e = D <= 128 ? launch_tile_persist(p, D, pool->num_cus, st) : launch_tile_kernel(p, D, st);
       if (e != hipSuccess) return IC_EHIP;
     }
-    if (p.n_row_items > p.n_vec_items) {
+    if (n_group_items > 0) {
       ProfScope ps_(pool, IC_K_GROUP, st);
       if (launch_group_kernel(p, D, st) != hipSuccess) return IC_EHIP;
     }
     if (p.n_vec_items > 0) {
       ProfScope ps_(pool, IC_K_ROW, st);
-      const int slots = pool->tune.row_slots > 0 ? pool->tune.row_slots : pool->num_cus;
-      const hipError_t e = pool->tune.row_launch == 3 && D <= 128 ? launch_row_persist_slim(p, D, slots, st)
-                           : pool->tune.row_launch != 1       ? launch_row_persist(p, D, slots, st)
+      const hipError_t e = pool->tune.row_launch == 3 && D <= 128 ? launch_row_persist_slim(p, D, row_slots, st)
+                           : pool->tune.row_launch != 1       ? launch_row_persist(p, D, row_slots, st)
                                                               : launch_row_kernel(p, D, st);
       if (e != hipSuccess) return IC_EHIP;
     }

@@ -81,16 +81,17 @@ struct AttnParams {
   int32_t n_merge_items;
   float scale_log2e;       // scale * log2(e): scores are kept in log2 units
   int32_t row_variant;     // row-kernel build: bit0 = prefetch depth 2, bit1 = plain (cached) loads
+  int32_t tile_first;      // persistent tile kernel: its waves ask for issue priority over the kernel beside it
   int32_t* counters;       // 16 work-queue counters, zero when the kernel starts
 };
 
 // Work-queue counters of the persistent kernels (16 ints at the head of the descriptor image):
-//   [0..7] tile queue of each XCD, [9] shared tile queue, [8] row queue, [12] / [13] workgroups of the
-//   row / tile kernel that have left.
+//   [0..7] tile queue of each XCD, [9] shared tile queue, [8] row queue, [10] queue of the slim group kernel,
+//   [12] / [13] / [14] workgroups of the row / tile / slim group kernel that have left.
 // A persistent kernel's workgroups leave through queue_leave: the last one out (every other has made
 // its final, failing pull by then) puts the kernel's counters back to zero, so that a descriptor
 // image already in device memory serves the next launch as it is.
-constexpr int kCtrRowQueue = 8, kCtrTileShared = 9, kCtrRowLeft = 12, kCtrTileLeft = 13;
+constexpr int kCtrRowQueue = 8, kCtrTileShared = 9, kCtrGroupQueue = 10, kCtrRowLeft = 12, kCtrTileLeft = 13, kCtrGroupLeft = 14;
 __device__ __forceinline__ void queue_leave(int32_t* counters, int first, int count, int extra, int left_slot) {
   if (threadIdx.x == 0) {
     const int gone = atomicAdd(&counters[left_slot], 1);
@@ -110,6 +111,8 @@ hipError_t launch_tile_persist(const AttnParams& p, int head_dim, int slots, hip
 hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_merge_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_group_kernel(const AttnParams& p, int head_dim, hipStream_t st);  // row items x K/V heads
+// The same items from a queue, built to share a CU with a tile workgroup: head_dim 128 and groups of 2..16 heads only.
+hipError_t launch_group_slim(const AttnParams& p, int head_dim, int slots, hipStream_t st);
 // Rows of k_new / v_new ([rows][H][D] bf16) into the pool at slot dst[row] (block * 16 + slot; < 0: skip).
 hipError_t launch_append(void* pool, const void* k_new, const void* v_new, const int32_t* dev_dst, int32_t rows,
                          int num_heads, int head_dim, hipStream_t st);

@@ -110,11 +110,13 @@ def test_every_launch_path(D, H):
     _check_batch(batch, 900 + D, tunings=tunings)
 
 
-@pytest.mark.parametrize("H,Hkv,D", [(8, 2, 64), (8, 1, 128), (16, 2, 128), (64, 8, 128), (6, 2, 128), (4, 2, 256), (64, 1, 64)])
+@pytest.mark.parametrize("H,Hkv,D", [(8, 2, 64), (8, 1, 128), (16, 2, 128), (64, 8, 128), (6, 2, 128), (4, 2, 256), (64, 1, 64),
+                                     (16, 1, 128), (4, 2, 128), (32, 1, 128)])
 def test_grouped_query_attention(H, Hkv, D):
     """H query heads over Hkv K/V heads: decode rows and spans, whole-row and split-KV plans, head groups
     of 2 to 32 on the MFMA path (keys staged once per group), a group of 3 (not a power of two) and one
-    of 64 on the per-head path, and the row-by-row plan."""
+    of 64 on the per-head path, and the row-by-row plan.  With head_dim 128 and groups of 2 to 16 the default
+    launch runs the slim group kernel beside the tile kernel, serial_spans = 1 the group kernel after it."""
     ctx = [700, 33, 300, 1, 129, 1000, 64, 515, 2100, 90, 17, 40]
     qlen = [200, 1, 300, 1, 128, 257, 1, 130, 1, 1, 1, 40]
     rng = np.random.default_rng(H * 7 + Hkv + D)
