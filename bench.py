@@ -493,9 +493,9 @@ def attention_kernel_names(pool, desc, acfg, args):
     beside = beside_rows or beside_group
     row = ("row_persist_slim_kernel" if beside or (args.row_launch == 3 and D <= 128) else
            "row_attn_kernel" if args.row_launch == 1 else "row_persist_kernel")
-    tile = "tile_persist_kernel" if D <= 128 else "tile_attn_kernel"
+    tile = f"tile_persist_kernel<{D}, {'true' if beside else 'false'}>" if D <= 128 else f"tile_attn_kernel<{D}>"
     group = "group_slim_kernel" if beside_group else f"group_attn_kernel<{D}>"
-    return {"row": f"{row}<{D}>", "group": group, "tile": f"{tile}<{D}>", "merge": f"merge_kernel<{D}>",
+    return {"row": f"{row}<{D}>", "group": group, "tile": tile, "merge": f"merge_kernel<{D}>",
             "side_by_side": beside}
 
 

@@ -27,7 +27,9 @@ __global__ __launch_bounds__(TW<D>::kThreads, (D <= 128 ? 2 : 1)) void tile_attn
 // Register budget: at most 216 per lane for head_dim <= 128 (checked by the test-suite from the
 // compiler's resource report).  Two waves of this kernel (432) and one of the slim row kernel (80)
 // fill the 512 of a SIMD exactly, which is what lets one workgroup of each share a CU.
-template <int D>
+// kBeside only names the build (side by side with a row or group kernel, or on its own), so that a kernel trace
+// tells the two uses apart; the code is the same.
+template <int D, bool kBeside>
 __global__ __launch_bounds__(TW<D>::kThreads, (D <= 128 ? 2 : 1)) void tile_persist_kernel(AttnParams p) {
   __shared__ __attribute__((aligned(16))) uint16_t lds[tile_lds_bytes<D>() / 2];
   __shared__ int s_next;
@@ -76,13 +78,15 @@ hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st)
 }
 
 // slots is rounded down to a multiple of 8 so that every XCD gets the same number of workgroups.
-hipError_t launch_tile_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st) {
+hipError_t launch_tile_persist(const AttnParams& p, int head_dim, int slots, bool beside, hipStream_t st) {
   if (p.n_tile_items <= 0) return hipSuccess;
   if (!p.counters || slots < 8) return hipErrorInvalidValue;
   const dim3 g((uint32_t)(slots - slots % 8));
-  switch (head_dim) {
-    case 64: hipLaunchKernelGGL(tile_persist_kernel<64>, g, dim3(TW<64>::kThreads), 0, st, p); break;
-    case 128: hipLaunchKernelGGL(tile_persist_kernel<128>, g, dim3(TW<128>::kThreads), 0, st, p); break;
+  switch (head_dim * 2 + (beside ? 1 : 0)) {
+    case 128: hipLaunchKernelGGL((tile_persist_kernel<64, false>), g, dim3(TW<64>::kThreads), 0, st, p); break;
+    case 129: hipLaunchKernelGGL((tile_persist_kernel<64, true>), g, dim3(TW<64>::kThreads), 0, st, p); break;
+    case 256: hipLaunchKernelGGL((tile_persist_kernel<128, false>), g, dim3(TW<128>::kThreads), 0, st, p); break;
+    case 257: hipLaunchKernelGGL((tile_persist_kernel<128, true>), g, dim3(TW<128>::kThreads), 0, st, p); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -706,7 +706,7 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
     bool ok = true;
     auto run_tile = [&] {
       ProfScope ps_(pool, IC_K_TILE, s_tile);
-      ok = launch_tile_persist(p, D, pool->num_cus, s_tile) == hipSuccess;
+      ok = launch_tile_persist(p, D, pool->num_cus, true, s_tile) == hipSuccess;
     };
     auto run_rows = [&] {
       if (ok && beside_group) {
@@ -740,12 +740,13 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
       // head_dim <= 128: the persistent launch also when no other kernel runs beside it.  Its per-XCD queues keep the
       // query tiles of one (sequence, head) on one L2: on 2048-row chunks the spans then fetch 2.6 x instead of 6.9 x
       // their keys from HBM and finish 7 % sooner (9.66 against 10.41 ms); shorter chunks and grouped pools: no change.
-      const hipError_t e = D <= 128 ? launch_tile_persist(p, D, pool->num_cus, st) : launch_tile_kernel(p, D, st);
+      const hipError_t e = D <= 128 ? launch_tile_persist(p, D, pool->num_cus, false, st) : launch_tile_kernel(p, D, st);
       if (e != hipSuccess) return IC_EHIP;
     }
     if (n_group_items > 0) {
       ProfScope ps_(pool, IC_K_GROUP, st);
-      if (launch_group_kernel(p, D, st) != hipSuccess) return IC_EHIP;
+      const bool slim = pool->tune.row_launch == 3 && D == 128 && p.group <= 16;  // the side-by-side build, alone
+      if ((slim ? launch_group_slim(p, D, row_slots, st) : launch_group_kernel(p, D, st)) != hipSuccess) return IC_EHIP;
     }
     if (p.n_vec_items > 0) {
       ProfScope ps_(pool, IC_K_ROW, st);

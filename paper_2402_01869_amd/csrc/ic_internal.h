@@ -107,7 +107,7 @@ __device__ __forceinline__ void queue_leave(int32_t* counters, int first, int co
 hipError_t launch_row_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_row_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st);
 hipError_t launch_row_persist_slim(const AttnParams& p, int head_dim, int slots, hipStream_t st);
-hipError_t launch_tile_persist(const AttnParams& p, int head_dim, int slots, hipStream_t st);
+hipError_t launch_tile_persist(const AttnParams& p, int head_dim, int slots, bool beside, hipStream_t st);
 hipError_t launch_tile_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_merge_kernel(const AttnParams& p, int head_dim, hipStream_t st);
 hipError_t launch_group_kernel(const AttnParams& p, int head_dim, hipStream_t st);  // row items x K/V heads

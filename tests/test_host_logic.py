@@ -344,8 +344,8 @@ def test_kernel_register_budgets():
                     usage[name][m.group(1)] = int(m.group(2))
     def find(kernel, dim):
         hits = [u for n, u in usage.items() if kernel in n and f"ILi{dim}E" in n]
-        assert len(hits) == 1, (kernel, dim, list(usage))
-        return hits[0]
+        assert len(hits) >= 1, (kernel, dim, list(usage))   # builds that differ in name only: the worst of them
+        return {k: max(h[k] for h in hits) for k in hits[0]}
     for dim in (64, 128):
         assert find("tile_persist_kernel", dim)["VGPRs"] <= 216
         assert find("row_persist_slim_kernel", dim)["VGPRs"] <= 80
