@@ -309,12 +309,19 @@ hipError_t launch_group_slim(const AttnParams& p, int head_dim, int slots, hipSt
   if (n_items <= 0) return hipSuccess;
   if (head_dim != kSD || p.group < 2 || p.group > 16 || !p.counters || slots < 1) return hipErrorInvalidValue;
   if ((uint64_t)n_items * (uint64_t)p.num_kv_heads > 0x7fffffffull) return hipErrorInvalidValue;
-  static std::once_flag once;  // more than 64 KiB of launch-time LDS has to be asked for, once per process
-  static hipError_t asked = hipSuccess;
-  std::call_once(once, [] {
-    asked = hipFuncSetAttribute((const void*)group_slim_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kSlimLdsBytes);
-  });
-  if (asked != hipSuccess) return asked;
+  {  // more than 64 KiB of launch-time LDS has to be asked for, once per device
+    static std::mutex mu;
+    static bool asked[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!asked[dev]) {
+      const hipError_t e =
+          hipFuncSetAttribute((const void*)group_slim_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kSlimLdsBytes);
+      if (e != hipSuccess) return e;
+      asked[dev] = true;
+    }
+  }
   hipLaunchKernelGGL(group_slim_kernel, dim3((uint32_t)slots), dim3(64 * kSlimWaves), kSlimLdsBytes, st, p);
   return hipGetLastError();
 }

@@ -123,7 +123,8 @@ def test_grouped_query_attention(H, Hkv, D):
     batch = W.assemble_batch(H, D, 16, 512, ctx, qlen, rng, num_kv_heads=Hkv)
     tunings = [dict(), dict(decode_part_tokens=64, span_part_tokens=128), dict(decode_part_tokens=256, span_part_tokens=64),
                dict(span_kernel=1), dict(span_kernel=1, decode_part_tokens=128), dict(serial_spans=1),
-               dict(span_kernel=2), dict(span_kernel=2, decode_part_tokens=64, span_part_tokens=64)]
+               dict(span_kernel=2), dict(span_kernel=2, decode_part_tokens=64, span_part_tokens=64),
+               dict(row_launch=3, serial_spans=1), dict(row_slots=5), dict(row_launch=3, serial_spans=1, row_slots=600)]
     _check_batch(batch, 300 + H + Hkv + D, tunings=tunings)
 
 
