@@ -486,15 +486,15 @@ def attention_kernel_names(pool, desc, acfg, args):
     D = acfg.head_dim
     G = acfg.num_heads // acfg.kv_heads
     grouped = 2 <= G <= 32 and G & (G - 1) == 0 and args.span_kernel == 0
-    pair = info["tile_items"] > 0 and not args.serial_spans and D <= 128
+    pair = info["tile_items"] > 0 and not args.serial_spans
     lay = pool.plan_image(desc)
     n_vec, n_group = lay["n_vector_row_items"], lay["n_row_items"] - lay["n_vector_row_items"]
     beside_rows = pair and n_vec > 0 and not grouped
     beside_group = pair and n_group > 0 and D == 128 and G <= 16
     beside = beside_rows or beside_group
-    row = ("row_persist_slim_kernel" if beside or (args.row_launch == 3 and D <= 128) else
+    row = ("row_persist_slim_kernel" if beside or args.row_launch == 3 else
            "row_attn_kernel" if args.row_launch == 1 else "row_persist_kernel")
-    tile = f"tile_persist_kernel<{D}, {'true' if beside else 'false'}>" if D <= 128 else f"tile_attn_kernel<{D}>"
+    tile = f"tile_persist_kernel<{D}, {'true' if beside else 'false'}>" if beside or D <= 128 else f"tile_attn_kernel<{D}>"
     group = "group_slim_kernel" if beside_group else f"group_attn_kernel<{D}>"
     return {"row": f"{row}<{D}>", "group": group, "tile": tile, "merge": f"merge_kernel<{D}>",
             "side_by_side": beside}

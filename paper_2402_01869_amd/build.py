@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libinfercept_hot.so")
 SOURCES = ["ic_api.hip", "kv_swap.hip", "swap_pipe.hip", "waste_model.hip", "attn_row.hip", "attn_tile.hip", "attn_group.hip", "attn_group_slim.hip",
            "ceilings.hip"]
-HEADERS = [os.path.join(CSRC, "ic_internal.h"), os.path.join(CSRC, "row_body.h"), os.path.join(CSRC, "tile_body.h"),
+HEADERS = [os.path.join(CSRC, "ic_internal.h"), os.path.join(CSRC, "row_body.h"), os.path.join(CSRC, "tile_body.h"), os.path.join(CSRC, "tile16_body.h"),
            os.path.join(os.path.dirname(HERE), "include", "infercept_hot.h"),
            os.path.join(os.path.dirname(HERE), "include", "infercept_measure.h")]
 

@@ -93,9 +93,10 @@ hipError_t launch_row_kernel(const AttnParams& p, int head_dim, hipStream_t st) 
 
 // Slim build of the persistent row kernel for running BESIDE the tile kernel: no register prefetch
 // (measured not to matter there: the CU's memory pipe, not the wave, holds the loads in flight)
-// and at most 80 VGPRs, so that one of these workgroups fits on a CU next to a tile workgroup.
+// and at most 80 VGPRs (head_dim 256: 96, with blocks taken in two halves), so that one of these workgroups fits
+// on a CU next to a tile workgroup.
 template <int D>
-__global__ __launch_bounds__(kRowWaves * 64, 6) void row_persist_slim_kernel(AttnParams p) {
+__global__ __launch_bounds__(kRowWaves * 64, (D <= 128 ? 6 : 5)) void row_persist_slim_kernel(AttnParams p) {
   __shared__ __attribute__((aligned(16))) float lds[row_lds_bytes<D>() / sizeof(float)];
   __shared__ int s_next;
   const int H = p.num_heads;
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(kRowWaves * 64, 6) void row_persist_slim_kernel(Att
     if (idx >= n_r) break;
     const uint32_t item = idx / (uint32_t)H;
     const RowItem it = p.row_items[item];
-    row_body<D, 0, true>(p, it, (int)(idx - item * (uint32_t)H), lds);
+    row_body<D, 0, true, (D > 128)>(p, it, (int)(idx - item * (uint32_t)H), lds);
     __syncthreads();
   }
   queue_leave(p.counters, kCtrRowQueue, 1, -1, kCtrRowLeft);
@@ -134,6 +135,7 @@ hipError_t launch_row_persist_slim(const AttnParams& p, int head_dim, int slots,
   switch (head_dim) {
     case 64: hipLaunchKernelGGL(row_persist_slim_kernel<64>, g, b, 0, st, p); break;
     case 128: hipLaunchKernelGGL(row_persist_slim_kernel<128>, g, b, 0, st, p); break;
+    case 256: hipLaunchKernelGGL(row_persist_slim_kernel<256>, g, b, 0, st, p); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

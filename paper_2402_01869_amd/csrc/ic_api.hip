@@ -281,8 +281,8 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   const int H = pool->cfg.num_heads, D = pool->cfg.head_dim;
   // Which of the two kernels of a side-by-side launch ends last, from the rates they reach there (tile kernel
   // 0.9 PFLOP/s at 4 D flop per pair and head, row kernels 5.5 TB/s at 4 D bytes per key and K/V head): that one
-  // goes on the caller's stream, the other through the fork and join of the second stream.
-  ps.tile_leads = tile_pairs * H * (4.0 * D / 0.9e15) > row_keys * pool->cfg.num_kv_heads * (4.0 * D / 5.5e12);
+  // goes on the caller's stream, the other through the fork and join of the second stream.  (head_dim 256: 0.5 PFLOP/s.)
+  ps.tile_leads = tile_pairs * H * (4.0 * D / (D > 128 ? 0.5e15 : 0.9e15)) > row_keys * pool->cfg.num_kv_heads * (4.0 * D / 5.5e12);
   size_t o = 0;
   ps.off_ctr = o;     o = align_up(o + sizeof(int32_t) * 16, 256);
   ps.off_bt_off = o;  o = align_up(o + sizeof(int32_t) * (size_t)d->num_seqs, 256);
@@ -679,10 +679,9 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
   // workgroup of each per CU, the tile kernel on the pool's second stream (forked from and joined
   // back into the caller's stream by events).  The kernel beside the tile kernel is the slim row
   // kernel (multi-head pools) or the slim group kernel (grouped pools: head_dim 128, groups of up
-  // to 16 heads).  serial_spans = 1, head_dim 256 (whose tile workgroup leaves no registers for a
-  // neighbour) and the other grouped shapes run one kernel after the other instead.
+  // to 16 heads).  serial_spans = 1 and the other grouped shapes run one kernel after the other instead.
   const int n_group_items = p.n_row_items - p.n_vec_items;
-  const bool pair_ok = p.n_tile_items > 0 && !pool->tune.serial_spans && D <= 128;
+  const bool pair_ok = p.n_tile_items > 0 && !pool->tune.serial_spans;
   const bool beside_rows = pair_ok && p.n_vec_items > 0 && !ps.decode_as_group;
   const bool beside_group = pair_ok && n_group_items > 0 && D == 128 && p.group <= 16;
   const int row_slots = pool->tune.row_slots > 0 ? pool->tune.row_slots : pool->num_cus;
@@ -740,6 +739,8 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
       // head_dim <= 128: the persistent launch also when no other kernel runs beside it.  Its per-XCD queues keep the
       // query tiles of one (sequence, head) on one L2: on 2048-row chunks the spans then fetch 2.6 x instead of 6.9 x
       // their keys from HBM and finish 7 % sooner (9.66 against 10.41 ms); shorter chunks and grouped pools: no change.
+      // head_dim 256: one workgroup per work item; the persistent build is held to 208 registers for the sake of
+      // its neighbour and is 19 % slower alone (0.197 against 0.166 ms on the GPT-J-shaped chunks).
       const hipError_t e = D <= 128 ? launch_tile_persist(p, D, pool->num_cus, false, st) : launch_tile_kernel(p, D, st);
       if (e != hipSuccess) return IC_EHIP;
     }
@@ -750,7 +751,7 @@ static int launch_attention(ic_pool* pool, const PlanSizes& ps, float scale, con
     }
     if (p.n_vec_items > 0) {
       ProfScope ps_(pool, IC_K_ROW, st);
-      const hipError_t e = pool->tune.row_launch == 3 && D <= 128 ? launch_row_persist_slim(p, D, row_slots, st)
+      const hipError_t e = pool->tune.row_launch == 3 ? launch_row_persist_slim(p, D, row_slots, st)
                            : pool->tune.row_launch != 1       ? launch_row_persist(p, D, row_slots, st)
                                                               : launch_row_kernel(p, D, st);
       if (e != hipSuccess) return IC_EHIP;

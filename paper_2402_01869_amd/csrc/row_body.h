@@ -61,24 +61,26 @@ struct Geo {
   static constexpr int kGroups = kRowWaves * kTokPerLoad;
 };
 
-template <int D>
+// NL loads of 1 KiB of K and of V: a whole (block, head) tile (NL = kLoads), or half of one.
+template <int D, int NL = Geo<D>::kLoads>
 struct Tile {
-  u32x4 k[Geo<D>::kLoads];
-  u32x4 v[Geo<D>::kLoads];
+  u32x4 k[NL];
+  u32x4 v[NL];
 };
 
-template <int D, bool NT>
-__device__ __forceinline__ void load_tile(Tile<D>& t, const char* pool, int64_t blk, int head,
-                                          int H, int lane) {
+// j0: first 1 KiB piece of the (block, head) tile to load (0 for a whole tile).
+template <int D, bool NT, int NL = Geo<D>::kLoads>
+__device__ __forceinline__ void load_tile(Tile<D, NL>& t, const char* pool, int64_t blk, int head,
+                                          int H, int lane, int j0 = 0) {
   constexpr int kTileBytes = kBlockSize * D * 2;
-  const char* kb = pool + ((blk * 2) * H + head) * (int64_t)kTileBytes + lane * 16;
+  const char* kb = pool + ((blk * 2) * H + head) * (int64_t)kTileBytes + lane * 16 + j0 * 1024;
   const char* vb = kb + (int64_t)H * kTileBytes;
 #pragma unroll
-  for (int j = 0; j < Geo<D>::kLoads; ++j)
+  for (int j = 0; j < NL; ++j)
     t.k[j] = NT ? __builtin_nontemporal_load((const u32x4*)(kb + j * 1024))
                 : *(const u32x4*)(kb + j * 1024);
 #pragma unroll
-  for (int j = 0; j < Geo<D>::kLoads; ++j)
+  for (int j = 0; j < NL; ++j)
     t.v[j] = NT ? __builtin_nontemporal_load((const u32x4*)(vb + j * 1024))
                 : *(const u32x4*)(vb + j * 1024);
 }
@@ -92,10 +94,10 @@ __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
                                          false);
 }
 
-template <int D, bool MASK>
-__device__ __forceinline__ void consume_tile(const Tile<D>& t, const u32x4& q2, float sc, float& m,
+// n_valid counts from the first token this Tile holds.
+template <int D, bool MASK, int NL = Geo<D>::kLoads>
+__device__ __forceinline__ void consume_tile(const Tile<D, NL>& t, const u32x4& q2, float sc, float& m,
                                              float& l, float (&acc)[8], int n_valid, int lane) {
-  constexpr int NL = Geo<D>::kLoads;
   float s[NL];
 #pragma unroll
   for (int j = 0; j < NL; ++j) {
@@ -148,10 +150,13 @@ constexpr int row_lds_bytes() {
 
 // One RowItem x one head, executed by a workgroup of 4 waves.  PF = tiles prefetched ahead,
 // NT = non-temporal KV loads.  lds: at least row_lds_bytes<D>() bytes of workgroup LDS.
-template <int D, int PF, bool NT>
+// HALF (with PF = 0 only): a block is loaded and consumed in two halves of 8 tokens, which halves the registers a
+// tile takes: the slim build for head_dim 256.
+template <int D, int PF, bool NT, bool HALF = false>
 __device__ __forceinline__ void row_body(const AttnParams& p, const RowItem& it, int head, float* lds) {
   using G = Geo<D>;
   constexpr int STAGES = PF + 1;  // register buffers
+  static_assert(!HALF || (PF == 0 && G::kLoads % 2 == 0), "half-block steps have no prefetch");
 
   const int H = p.num_heads;
   const int Hk = p.num_kv_heads;
@@ -177,6 +182,25 @@ __device__ __forceinline__ void row_body(const AttnParams& p, const RowItem& it,
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
 
   const char* pool = (const char*)p.pool;
+  if constexpr (HALF) {
+    constexpr int NH = G::kLoads / 2;            // 1 KiB pieces per half
+    constexpr int kHalfTok = kBlockSize / 2;
+    for (int i = 0; i < nb_w; ++i) {
+      const int id = __builtin_amdgcn_readlane(my_id, i);
+      const int tok0 = k_begin + (w + kRowWaves * i) * kBlockSize;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int n_valid = k_end - tok0 - h * kHalfTok;
+        if (n_valid <= 0) break;  // wave-uniform
+        Tile<D, NH> t;
+        load_tile<D, NT, NH>(t, pool, id, kvh, Hk, lane, h * NH);
+        if (n_valid >= kHalfTok)
+          consume_tile<D, false, NH>(t, q2, sc, m, l, acc, kHalfTok, lane);
+        else
+          consume_tile<D, true, NH>(t, q2, sc, m, l, acc, n_valid, lane);
+      }
+    }
+  } else {
   Tile<D> buf[STAGES];
 #pragma unroll
   for (int s = 0; s < PF; ++s)
@@ -198,6 +222,7 @@ __device__ __forceinline__ void row_body(const AttnParams& p, const RowItem& it,
           consume_tile<D, true>(buf[s], q2, sc, m, l, acc, n_valid, lane);
       }
     }
+  }
   }
 
   // combine the lane groups of all waves through LDS

@@ -1,6 +1,7 @@
 // Tile path of the attention kernels: the query rows of a recomputation chunk (Section 4.2) against a range of their
 // sequence's paged keys.  Here QK^T and PV are dense contractions (hundreds of rows share every
-// key), so they run on the matrix cores: v_mfma_f32_32x32x16_bf16, fp32 accumulation.
+// key), so they run on the matrix cores: v_mfma_f32_32x32x16_bf16, fp32 accumulation.  (The kernels use this body for
+// head_dim 64 and 128; head_dim 256 runs tile16_body.h, where a wave takes 16 rows.)
 //
 // One workgroup = one TileItem x one head group (one head with multi-head attention; with grouped
 // queries the G heads that share a K/V head): up to tile_rows(D) rows = query rows x heads of the

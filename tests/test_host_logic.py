@@ -318,8 +318,9 @@ def test_saturation_point_and_schedule_match_the_oracle():
 def test_kernel_register_budgets():
     """The side-by-side launch of the mixed batch needs, per SIMD, two waves of the persistent tile kernel
     and one of the slim row kernel resident together: 2 x 216 + 80 = 512 registers per lane; in a grouped pool
-    the slim group kernel takes the row kernel's place with 96, so the tile kernel may use 208 there.  Read the
-    compiler's resource report for these kernels (head_dim 64 and 128) and for spills in the MFMA kernels."""
+    the slim group kernel takes the row kernel's place with 96, so the tile kernel may use 208 there; head_dim 256
+    pairs a 208-register tile kernel of 16-row waves with a 96-register row kernel.  Read the compiler's resource
+    report for these kernels and for spills in the MFMA kernels."""
     import shutil
     import subprocess
     import tempfile
@@ -349,6 +350,8 @@ def test_kernel_register_budgets():
     for dim in (64, 128):
         assert find("tile_persist_kernel", dim)["VGPRs"] <= 216
         assert find("row_persist_slim_kernel", dim)["VGPRs"] <= 80
+    # head_dim 256: 16-row waves, 2 x 208 + 96
+    assert find("tile_persist_kernel", 256)["VGPRs"] <= 208 and find("row_persist_slim_kernel", 256)["VGPRs"] <= 96
     slim = [u for n, u in usage.items() if "group_slim_kernel" in n]
     assert len(slim) == 1 and slim[0]["VGPRs"] <= 96 and 2 * find("tile_persist_kernel", 128)["VGPRs"] + 96 <= 512
     for dim in (64, 128, 256):
