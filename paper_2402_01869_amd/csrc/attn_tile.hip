@@ -14,6 +14,7 @@ template <int D, bool k16 = (D > 128)>
 struct Impl {
   static constexpr int kThreads = TW<D>::kThreads;
   static constexpr int kLdsBytes = tile_lds_bytes<D>();
+  template <bool kAlone>
   static __device__ __forceinline__ void body(const AttnParams& p, const TileItem& it, int th, uint16_t* lds) {
     tile_body<D>(p, it, th, lds);
   }
@@ -22,8 +23,9 @@ template <int D>
 struct Impl<D, true> {
   static constexpr int kThreads = tile16::G16<D>::kThreads;
   static constexpr int kLdsBytes = tile16::tile16_lds_bytes<D>();
+  template <bool kAlone>  // a kernel with its SIMDs to itself has registers for the pinned operand prefetch
   static __device__ __forceinline__ void body(const AttnParams& p, const TileItem& it, int th, uint16_t* lds) {
-    tile16::tile16_body<D>(p, it, th, lds);
+    tile16::tile16_body<D, kAlone>(p, it, th, lds);
   }
 };
 
@@ -35,7 +37,7 @@ __global__ __launch_bounds__(Impl<D>::kThreads, 2) void tile_attn_kernel(AttnPar
   const int item_idx = wg / n_th;
   const int th = wg - item_idx * n_th;
   const TileItem it = p.tile_items[item_idx];
-  Impl<D>::body(p, it, th, lds);
+  Impl<D>::template body<true>(p, it, th, lds);
 }
 
 // Persistent launch of the same body, for running beside the row kernel: `slots` workgroups (one
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(Impl<D>::kThreads, 2) __attribute__((amdgpu_num_vgp
       th = idx - item * (uint32_t)H;
     }
     const TileItem it = p.tile_items[item];
-    Impl<D>::body(p, it, (int)th, lds);
+    Impl<D>::template body<false>(p, it, (int)th, lds);
     __syncthreads();  // the body leaves LDS in use until every wave is through
   }
   queue_leave(p.counters, 0, 8, kCtrTileShared, kCtrTileLeft);

@@ -25,8 +25,12 @@ struct G16 {
   static constexpr int kRows = 16;                        // query rows (x heads of a group) per wave
   static constexpr int kWaves = tile_rows(D) / kRows;     // 8 for head_dim 256
   static constexpr int kThreads = 64 * kWaves;
-  static constexpr int kKStride = TG<D>::kKStride;        // bf16 per LDS row of K / of V: as in tile_body.h
-  static constexpr int kVStride = TG<D>::kVStride;
+  // bf16 per LDS row of K and of V: rows shift by 8 of the 64 banks (32 bytes).  An operand read of K takes 16 bytes of
+  // 16 keys per quarter wave, a transpose read of V 32 bytes of 8 keys per half wave: both then cover all banks once
+  // (measured: with the 16-byte shift of tile_body.h the K reads of this layout are 5 % slower, with its 64-byte
+  // shift the V reads conflict two ways).
+  static constexpr int kKStride = D + 16;
+  static constexpr int kVStride = D + 16;
   static constexpr int kChunks = D / 8;                   // 16-byte chunks per token row
   static constexpr int kLoads = kTileK * kChunks / kThreads;  // K (and V) chunks per thread and tile
   static constexpr int kQSteps = D / 32;                  // MFMA k-steps of Q K^T
@@ -93,7 +97,9 @@ __device__ __forceinline__ bf16x8 read_vt16(const uint16_t* vs, int d0, int h, i
 }
 
 // One 64-key tile for one wave.  mask is set only for tiles that straddle the wave's causal diagonal.
-template <int D>
+// kPin: pin the order of operand reads and MFMAs written here (costs about ten registers; the build that shares its
+// SIMDs with another kernel cannot afford them).
+template <int D, bool kPin>
 __device__ __forceinline__ void wave_step16(const uint16_t* ks, const uint16_t* vs, const bf16x8 (&qreg)[G16<D>::kQSteps],
                                             f32x4 (&acc_o)[G16<D>::kDTiles], float& m, float& l, int kt, int pos, int lane,
                                             float sc, bool mask) {
@@ -103,15 +109,33 @@ __device__ __forceinline__ void wave_step16(const uint16_t* ks, const uint16_t* 
 #pragma unroll
   for (int u = 0; u < 4; ++u) s[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
   {
-    // the four 16-key subtiles advance together: four independent accumulators alternate in the matrix pipe
+    // The four 16-key subtiles advance together (four independent accumulators alternate in the matrix pipe), and the
+    // A operands of the next k-step are read from LDS before this step's MFMAs issue: the kernel is bound by LDS
+    // operand reads, and left to itself the compiler keeps only one or two of them in flight per wave.
     const uint16_t* kp = ks + col * G::kKStride + 8 * g;
+    bf16x8 a[4];
 #pragma unroll
-    for (int t = 0; t < G::kQSteps; ++t)
+    for (int u = 0; u < 4; ++u) a[u] = *(const bf16x8*)(kp + 16 * u * G::kKStride);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const bf16x8 a = *(const bf16x8*)(kp + 16 * u * G::kKStride + 32 * t);
-        s[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qreg[t], s[u], 0, 0, 0);
+    for (int t = 0; t < G::kQSteps; ++t) {
+      bf16x8 n[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) n[u] = t + 1 < G::kQSteps ? *(const bf16x8*)(kp + 16 * u * G::kKStride + 32 * (t + 1)) : a[u];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) s[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], qreg[t], s[u], 0, 0, 0);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) a[u] = n[u];
+    }
+    // pin that order (0x100: LDS reads, 0x008: MFMAs): the scheduler otherwise moves every read next to its use
+    if constexpr (kPin) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int t = 0; t + 1 < G::kQSteps; ++t) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    }
   }
   // this lane: query column col, keys kt + 16 u + 4 g + i
   if (mask) {  // wave-uniform; the empty asm keeps this a branch instead of 16 always-on selects
@@ -155,14 +179,28 @@ __device__ __forceinline__ void wave_step16(const uint16_t* ks, const uint16_t* 
       pb[u >> 1][4 * (u & 1) + i] = pr[0];
       pb[u >> 1][4 * (u & 1) + i + 1] = pr[1];
     }
-  // O^T += V^T P^T: the 32-key half outer, so that the kDTiles independent accumulators alternate
+  // O^T += V^T P^T: the 32-key half outer, so that the kDTiles independent accumulators alternate; operands are
+  // read four MFMAs ahead.
+  {
+    constexpr int kAhead = 4, kOps = 2 * G::kDTiles;
+    bf16x8 a[kAhead];
 #pragma unroll
-  for (int h = 0; h < 2; ++h)
+    for (int i = 0; i < kAhead; ++i) a[i] = read_vt16<D>(vs, 16 * (i % G::kDTiles), i / G::kDTiles, lane);
 #pragma unroll
-    for (int dt = 0; dt < G::kDTiles; ++dt) {
-      const bf16x8 a = read_vt16<D>(vs, 16 * dt, h, lane);
-      acc_o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[h], acc_o[dt], 0, 0, 0);
+    for (int i = 0; i < kOps; ++i) {
+      const bf16x8 cur = a[i % kAhead];
+      if (i + kAhead < kOps) a[i % kAhead] = read_vt16<D>(vs, 16 * ((i + kAhead) % G::kDTiles), (i + kAhead) / G::kDTiles, lane);
+      acc_o[i % G::kDTiles] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur, pb[i / G::kDTiles], acc_o[i % G::kDTiles], 0, 0, 0);
     }
+    if constexpr (kPin) {  // two transpose loads per operand
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0);
+#pragma unroll
+      for (int i = 0; i < kOps; ++i) {
+        if (i + kAhead < kOps) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      }
+    }
+  }
 }
 
 template <int D>
@@ -176,7 +214,7 @@ constexpr int tile16_lds_bytes() {
 
 // One TileItem x one group of (1 << p.tile_g_shift) query heads that share a K/V head, executed by a workgroup of
 // tile_rows(D) / 16 waves (see tile_body in tile_body.h for the row mapping).  lds: tile16_lds_bytes<D>() bytes.
-template <int D>
+template <int D, bool kPin>
 __device__ __forceinline__ void tile16_body(const AttnParams& p, const TileItem& it, int th, uint16_t* lds) {
   using G = G16<D>;
   const int H = p.num_heads, Hk = p.num_kv_heads, gs = p.tile_g_shift;
@@ -242,7 +280,7 @@ __device__ __forceinline__ void tile16_body(const AttnParams& p, const TileItem&
     };
     if (copy_first) copy();
     if (kt <= wave_pos_hi)  // otherwise every key of the tile is in this wave's future
-      wave_step16<D>(ks, vs, qreg, acc_o, m, l, kt, pos, lane, sc, kt + kTileK - 1 > wave_pos_lo);
+      wave_step16<D, kPin>(ks, vs, qreg, acc_o, m, l, kt, pos, lane, sc, kt + kTileK - 1 > wave_pos_lo);
     if (!copy_first) copy();
     fetch_tile16<D>(st, pool, ids, kvh, Hk, tid);
     tile_ids(t + 3, ids);
