@@ -175,7 +175,7 @@ int ic_check_batch(const ic_pool_cfg* cfg, const ic_batch_desc* desc);
 /* Launch plan knobs.  Partition sizes are in tokens and are rounded up to a multiple of 64;
  * 0 keeps the built-in choice.  Smaller values force the split-KV path on short contexts. */
 typedef struct {
-  int32_t decode_part_tokens; /* keys per work item of a decode row                          */
+  int32_t decode_part_tokens; /* keys per work item of a decode row (built-in: 4096)         */
   int32_t span_part_tokens;   /* keys per work item of a span's query tile (built-in: 8192, or no split at all
                                  when the unsplit tiles already give every CU four workgroups) */
   int32_t span_kernel;        /* 0 = built-in choice (spans: MFMA tiles; decode rows: vector kernel, or the MFMA
@@ -186,8 +186,10 @@ typedef struct {
                                  two persistent kernels side by side (the tile kernel on the pool's own stream) */
   int32_t row_launch;         /* single-role row kernel: 0 = built-in choice (persistent, one workgroup per CU),
                                  1 = one workgroup per work item, 2 = persistent, 3 = persistent, the slim
-                                 build that runs beside the tile kernel (head_dim <= 128)     */
-  int32_t row_slots;          /* resident workgroups of the persistent row kernel; 0 = one per CU */
+                                 builds that otherwise run beside the tile kernel (in a grouped-query pool of
+                                 head_dim 128 with groups of up to 16: the slim group kernel)  */
+  int32_t row_slots;          /* resident workgroups of the persistent row kernel (and of the slim group kernel);
+                                 0 = one per CU */
   int32_t mfma_min_keys;      /* query rows that see fewer keys than this run on the vector kernel, which keeps the
                                  softmax weights in fp32 (the matrix-core kernels round them to bf16, and with a
                                  handful of keys one weight's rounding shows in the output); 0 = built-in 64,

@@ -14,9 +14,9 @@ using namespace ic;
 namespace {
 
 constexpr int kStagingSlots = 4;       // pinned host buffers cycled by successive calls
-// Keys per decode work item: 4096 (the most a row item can hold), 512 for head_dim 256.  Measured on the 13B-shaped
-// batches: contexts up to 4096 keys as ONE item each (no partial results, no merge pass) are 1 % faster than 2048-key
-// items, alone and beside the tile kernel; 512- and 1024-key items are 1-5 % slower.
+// Keys per decode work item: 4096 (the most a row item can hold).  Measured on the 13B-shaped batches: contexts up to
+// 4096 keys as ONE item each (no partial results, no merge pass) are 1 % faster than 2048-key items, alone and beside
+// the tile kernel; 512- and 1024-key items are 1-5 % slower (head_dim 256, GPT-J-shaped decode: 6 % slower at 512).
 constexpr int kDefaultRowPart = 4096;
 constexpr int kDefaultSpanPart = 8192; // keys per span-tile work item (partials of 256 rows are costly)
 constexpr int kUnsplitWorkgroups = 1024;  // tile workgroups (4 per CU) from which spans are not split at all
@@ -229,8 +229,7 @@ void plan_sizes(const ic_pool* pool, const ic_batch_desc* d, PlanSizes& ps) {
   const int kTileRows = tile_rows(pool->cfg.head_dim) >> ps.tile_g_shift;
   ps.tile_rows = kTileRows;
   const ic_tuning& t = pool->tune;
-  ps.row_part = t.decode_part_tokens > 0 ? round64(t.decode_part_tokens)
-                                         : (pool->cfg.head_dim >= 256 ? 512 : kDefaultRowPart);
+  ps.row_part = t.decode_part_tokens > 0 ? round64(t.decode_part_tokens) : kDefaultRowPart;
   ps.row_part = std::min(ps.row_part, kMaxRowPart);
   ps.span_part = t.span_part_tokens > 0 ? round64(t.span_part_tokens) : kDefaultSpanPart;
   ps.min_keys = t.mfma_min_keys > 0 ? std::min(t.mfma_min_keys, 64) : kMfmaMinKeys;  // <= the smallest partition

@@ -161,7 +161,7 @@ def test_full_size_plans_are_sane():
         info = p.plan_query(d)
         assert info["decode_rows"] == cfg.n_decode and info["span_rows"] == cfg.n_span * cfg.span_len
         assert info["table_entries"] == int(sum(-(-int(c) // 16) for c in b.ctx_len))
-        part = 512 if cfg.head_dim == 256 else 4096
+        part = 4096
         assert info["row_items"] == int(sum(-(-int(c) // part) for c in b.ctx_len[:cfg.n_decode]))
         assert info["tile_items"] >= cfg.n_span * (cfg.span_len // 256)
         assert 0 < p.workspace_bytes(d) < (4 << 30)
