@@ -24,9 +24,9 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, vendor figure
 # figures and commands in the profiles/ file named next to each.  Only valid for the default launch plan of
 # these workloads; the JSON line says where the figure comes from (`traffic_source`).
 MEASURED_TRAFFIC = {"mixed_13b/row": ((2837482 * 2.0 + 1968) * 1024, "profiles/row_and_tile_persist_kernels_mixed_13b.md"),
-                    "gptj_decode/row": ((660561 * 2.0 + 3275) * 1024, "profiles/row_persist_kernel_gptj_decode.md"),
-                    "gptj_mixed/tile": ((205729 * 2.0 + 32768) * 1024, "profiles/tile_and_row_kernels_gptj_mixed.md"),
-                    "gptj_mixed/row": ((638108 * 2.0 + 3200) * 1024, "profiles/tile_and_row_kernels_gptj_mixed.md"),
+                    "gptj_decode/row": ((660150 * 2.0 + 560) * 1024, "profiles/row_persist_kernel_gptj_decode.md"),
+                    "gptj_mixed/tile": ((154356 * 2.0 + 34851) * 1024, "profiles/tile_and_row_kernels_gptj_mixed.md"),
+                    "gptj_mixed/row": ((635748 * 2.0 + 560) * 1024, "profiles/tile_and_row_kernels_gptj_mixed.md"),
                     "gqa_70b/group": ((542050 * 2.0 + 5424) * 1024, "profiles/group_and_tile_kernels_gqa_70b.md"),
                     "gqa_70b/tile": ((124557 * 2.0 + 65610) * 1024, "profiles/group_and_tile_kernels_gqa_70b.md"),
                     "long_ctx/tile": ((6047503 * 2.0 + 262353) * 1024, "profiles/tile_persist_kernel_long_ctx.md")}
